@@ -1,0 +1,601 @@
+// bf16 production kernels for gfx950 (CDNA4, wave64).
+//
+// Decode at batch sizes 8..128 is a weight- and KV-streaming problem: every
+// projection reads its whole weight matrix once per step and every attention
+// head reads its whole KV history once per step, with O(batch) flops per byte.
+// The kernels are therefore organised around 16-byte-per-lane, fully coalesced
+// streams that land directly in the register layout of
+// v_mfma_f32_16x16x32_bf16 (no LDS round trip for streamed data):
+//   * weights are stored "fragment-major" (see skd_kernels.h) so one
+//     wave-wide load = one 16x32 MFMA A-operand;
+//   * activations use the same layout with batch rows in place of weight rows
+//     (B-operand);
+//   * K is stored per 16-key tile as A-operand fragments (keys x head_dim),
+//     V per 32-key block as A-operand fragments of V^T (head_dim x keys) with
+//     the key order inside a block chosen so that the softmax weights leave
+//     the QK^T accumulator already in B-operand position.
+#include "skd_kernels.h"
+
+namespace skd {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t uint32x4;
+
+__device__ inline uint32_t f2bf(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ inline float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ inline uint32_t pack2(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
+
+__device__ inline float wave_sum_f(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline float block_sum_f(float v, float *sh) {
+  v = wave_sum_f(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = 0;
+  for (unsigned w = 0; w < (blockDim.x >> 6); ++w) r += sh[w];
+  return r;
+}
+
+__device__ inline long d_frag_index(long row, long col, long K) {
+  return (((row >> 4) * (K >> 5) + (col >> 5)) * 64 + (row & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7);
+}
+
+// ------------------------------------------------------------------ KV page addressing
+// Page (one batch row, one layer): [head][32-key block][K block | V block],
+// K block = [tile 0..1][chunk 0..dh/32-1][lane][8], V block = [dh/16][lane][8].
+__device__ inline long kv_block_base(int h, int tt, const KvGeom &g) {
+  return (long)h * (g.page_tokens * g.dh * 2) + (long)(tt >> 5) * (64 * g.dh);
+}
+__device__ inline long kv_k_off(int h, int tt, int e, const KvGeom &g) {
+  const int kk = tt & 31;
+  return kv_block_base(h, tt, g) +
+         ((long)((kk >> 4) * (g.dh >> 5) + (e >> 5)) * 64 + (kk & 15) + 16 * ((e & 31) >> 3)) * 8 + (e & 7);
+}
+__device__ inline long kv_v_off(int h, int tt, int e, const KvGeom &g) {
+  const int kk = tt & 31;
+  return kv_block_base(h, tt, g) + 32 * g.dh +
+         ((long)(e >> 4) * 64 + 16 * ((kk & 15) >> 2) + (e & 15)) * 8 + 4 * (kk >> 4) + (kk & 3);
+}
+
+// ------------------------------------------------------------------ skinny GEMM
+// C[b][n] = sum_k A[b][k] * W[n][k], batch on the MFMA column side.
+// Workgroup = 4 waves that split the workgroup's K range and share the same
+// 16*R weight rows; grid.y splits K further across workgroups.  Each wave
+// streams R weight-fragment rows and MB activation fragments per 32-wide
+// k-step with two register buffers of U k-steps (loads for the next buffer are
+// in flight while the MFMAs of the current one issue).
+template <int EPI>
+__device__ inline void gemm_epilogue(const GemmArgs &a, int b, int n0, floatx4 v, int grp);
+
+template <>
+__device__ inline void gemm_epilogue<EPI_PARTIAL>(const GemmArgs &a, int b, int n0, floatx4 v, int) {
+  if (n0 + 3 < a.N) {
+    *(floatx4 *)&a.partial[((long)blockIdx.y * a.B_pad + b) * a.N + n0] = v;
+  }
+}
+
+template <>
+__device__ inline void gemm_epilogue<EPI_QKV>(const GemmArgs &a, int b, int n0, floatx4 v, int) {
+  if (n0 >= a.N) return;
+  for (int i = 0; i < 4; ++i) v[i] += a.bias[n0 + i];
+  const int which = n0 / a.d, within = n0 - which * a.d;
+  if (which == 0) {
+    uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+    *(uint2 *)&a.q_out[(long)b * a.d + within] = pk;
+    return;
+  }
+  if (b >= a.B) return;  // padded batch rows own no KV pages
+  const int h = within / a.kv.dh, e = within - h * a.kv.dh;
+  const int page = a.bt_layer[(long)b * a.kv.max_pages + a.t / a.kv.page_tokens];
+  bf16_t *pg = a.kv_pool + (long)page * a.kv.page_elems;
+  const int tt = a.t % a.kv.page_tokens;
+  if (which == 1) {
+    uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+    *(uint2 *)&pg[kv_k_off(h, tt, e, a.kv)] = pk;  // 4 consecutive head-dim elements share one lane slot
+  } else {
+    for (int i = 0; i < 4; ++i) pg[kv_v_off(h, tt, e + i, a.kv)] = (bf16_t)f2bf(v[i]);
+  }
+}
+
+template <>
+__device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0, floatx4 v, int) {
+  if (n0 >= a.N) return;
+  for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i] + a.bias[n0 + i], 0.f);
+  uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+  *(uint2 *)&a.act_out[d_frag_index(b, n0, a.N)] = pk;
+}
+
+template <int MB, int R, int EPI>
+__global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
+  constexpr int U = (R * MB >= 8) ? 1 : 2;  // k-steps per register buffer
+  constexpr int RM = R * MB;
+  extern __shared__ floatx4 red[];  // [4 waves][RM][64 lanes]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int Kf = a.K >> 5;
+  const int slots = a.split * 4, slot = blockIdx.y * 4 + wave;
+  const int kf0 = (int)((long)Kf * slot / slots), kf1 = (int)((long)Kf * (slot + 1) / slots);
+  const bf16x8 *Wb = (const bf16x8 *)a.W + ((long)blockIdx.x * R * Kf) * 64 + lane;
+  const bf16x8 *Ab = (const bf16x8 *)a.A + lane;
+
+  floatx4 acc[R][MB];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int m = 0; m < MB; ++m) acc[r][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  bf16x8 w0[U][R], x0[U][MB], w1[U][R], x1[U][MB];
+  auto load = [&](int kf, bf16x8(&w)[U][R], bf16x8(&x)[U][MB]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) w[u][r] = Wb[((long)r * Kf + kf + u) * 64];
+#pragma unroll
+      for (int m = 0; m < MB; ++m) x[u][m] = Ab[((long)m * Kf + kf + u) * 64];
+    }
+  };
+  auto fma = [&](bf16x8(&w)[U][R], bf16x8(&x)[U][MB]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+          acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u][r], x[u][m], acc[r][m], 0, 0, 0);
+  };
+
+  int kf = kf0;
+  const int nfull = (kf1 - kf0) / U;  // whole buffers
+  if (nfull > 0) {
+    load(kf, w0, x0);
+    int i = 0;
+    for (; i + 2 <= nfull; i += 2) {  // two buffers per trip
+      load(kf + U, w1, x1);
+      fma(w0, x0);
+      if (i + 2 < nfull) load(kf + 2 * U, w0, x0);
+      fma(w1, x1);
+      kf += 2 * U;
+    }
+    if (i < nfull) {  // odd buffer left; it was loaded into w0/x0
+      fma(w0, x0);
+      kf += U;
+    }
+  }
+  for (; kf < kf1; ++kf) {  // remainder k-steps (U == 2 only)
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const bf16x8 wv = Wb[((long)r * Kf + kf) * 64];
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+        acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, Ab[((long)m * Kf + kf) * 64], acc[r][m], 0, 0, 0);
+    }
+  }
+
+  // sum the four waves' partial tiles in a fixed order (deterministic)
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int m = 0; m < MB; ++m) red[(wave * RM + r * MB + m) * 64 + lane] = acc[r][m];
+  __syncthreads();
+
+  if constexpr (EPI == EPI_LOGITS) {
+    __shared__ float cv[RM][16];
+    __shared__ int ci[RM][16];
+    for (int p = wave; p < RM; p += 4) {
+      floatx4 v = red[p * 64 + lane];
+      for (int w = 1; w < 4; ++w) v += red[(w * RM + p) * 64 + lane];
+      const int r = p / MB, m = p % MB;
+      const int b = m * 16 + (lane & 15);
+      const int n0 = (blockIdx.x * R + r) * 16 + 4 * (lane >> 4);
+      float best = -3.0e38f;
+      int bi = 0x7fffffff;
+      for (int i = 0; i < 4; ++i) {
+        if (n0 + i < a.N) {
+          if (a.logits && b < a.B) a.logits[(long)b * a.N + n0 + i] = v[i];
+          if (v[i] > best) { best = v[i]; bi = n0 + i; }
+        }
+      }
+      for (int o = 16; o < 64; o <<= 1) {  // across the four 4-row groups of this column
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      if (lane < 16) { cv[p][lane] = best; ci[p][lane] = bi; }
+    }
+    __syncthreads();
+    if (threadIdx.x < MB * 16) {
+      const int m = threadIdx.x >> 4, c = threadIdx.x & 15;
+      float best = cv[m][c];
+      int bi = ci[m][c];
+      for (int r = 1; r < R; ++r) {
+        const float ov = cv[r * MB + m][c];
+        const int oi = ci[r * MB + m][c];
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      a.pmax[(long)blockIdx.x * a.B_pad + m * 16 + c] = best;
+      a.pidx[(long)blockIdx.x * a.B_pad + m * 16 + c] = bi;
+    }
+  } else {
+    for (int p = wave; p < RM; p += 4) {
+      floatx4 v = red[p * 64 + lane];
+      for (int w = 1; w < 4; ++w) v += red[(w * RM + p) * 64 + lane];
+      const int r = p / MB, m = p % MB;
+      gemm_epilogue<EPI>(a, m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
+    }
+  }
+}
+
+int bf16_gemm_groups(int N, int R) { return (N + 16 * R - 1) / (16 * R); }
+
+template <int MB, int R>
+static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid, size_t lds) {
+  switch (epi) {
+    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL>), grid, dim3(256), lds, s, a); break;
+    case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV>), grid, dim3(256), lds, s, a); break;
+    case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU>), grid, dim3(256), lds, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS>), grid, dim3(256), lds, s, a); break;
+  }
+}
+template <int MB>
+static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, dim3 grid) {
+  const size_t lds = (size_t)4 * R * MB * 64 * sizeof(floatx4);
+  if (R == 1) launch_gemm_epi<MB, 1>(s, a, epi, grid, lds);
+  else if (R == 2) launch_gemm_epi<MB, 2>(s, a, epi, grid, lds);
+  else launch_gemm_epi<MB, 4>(s, a, epi, grid, lds);
+}
+
+// Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}; the
+// cross-wave reduction buffer (4 * R * MB KiB of LDS) caps R for wide batches.
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R) {
+  const int MB = a.B_pad / 16;
+  if (MB >= 8) R = 1;
+  else if (MB >= 4 && R > 2) R = 2;
+  const int groups = bf16_gemm_groups(a.N, R);
+  const dim3 grid(groups, epi == EPI_LOGITS ? 1 : a.split);
+  switch (MB) {
+    case 1: launch_gemm_r<1>(s, a, epi, R, grid); break;
+    case 2: launch_gemm_r<2>(s, a, epi, R, grid); break;
+    case 4: launch_gemm_r<4>(s, a, epi, R, grid); break;
+    case 8: launch_gemm_r<8>(s, a, epi, R, grid); break;
+    default: return -1;
+  }
+  return groups;
+}
+
+// ------------------------------------------------------------------ embedding + first LayerNorm
+__global__ __launch_bounds__(256) void k_embed_ln(const int32_t *tokens, const int32_t *start, int t,
+                                                  const bf16_t *tok_emb, const bf16_t *pos_emb, const float *g,
+                                                  const float *bt, float *x, bf16_t *a_out, int d, int V) {
+  extern __shared__ float row[];
+  __shared__ float sh[4];
+  const int b = blockIdx.x;
+  int tok = tokens[b];
+  tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+  int pos = t - start[b];  // number of real tokens before this column
+  if (pos < 0) pos = 0;    // padding column, never attended to
+  float s = 0;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    const float v = bf2f(tok_emb[(long)tok * d + k]) + bf2f(pos_emb[(long)pos * d + k]);
+    row[k] = v;
+    x[(long)b * d + k] = v;
+    s += v;
+  }
+  const float mean = block_sum_f(s, sh) / d;
+  float q = 0;
+  for (int k = threadIdx.x; k < d; k += 256) q += (row[k] - mean) * (row[k] - mean);
+  const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
+  for (int k8 = threadIdx.x; k8 < d / 8; k8 += 256) {
+    uint32_t pk[4];
+    for (int j = 0; j < 4; ++j) {
+      const int k = k8 * 8 + 2 * j;
+      pk[j] = pack2((row[k] - mean) * rstd * g[k] + bt[k], (row[k + 1] - mean) * rstd * g[k + 1] + bt[k + 1]);
+    }
+    *(uint32x4 *)&a_out[d_frag_index(b, k8 * 8, d)] = uint32x4{pk[0], pk[1], pk[2], pk[3]};
+  }
+}
+
+void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
+                   const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
+                   int V) {
+  hipLaunchKernelGGL(k_embed_ln, dim3(B), dim3(256), d * sizeof(float), s, tokens, start, t, tok_emb, pos_emb, g, b,
+                     x, a_out, d, V);
+}
+
+// ------------------------------------------------------------------ split-K reduce + bias + residual + LayerNorm
+__global__ __launch_bounds__(256) void k_reduce_ln(const float *partial, int split, int B_pad, const float *bias,
+                                                   float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
+  extern __shared__ float row[];
+  __shared__ float sh[4];
+  const int b = blockIdx.x;
+  float s = 0;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    float v = partial[(long)b * d + k];
+    for (int sp = 1; sp < split; ++sp) v += partial[((long)sp * B_pad + b) * d + k];  // fixed order
+    v = x[(long)b * d + k] + (v + bias[k]);
+    row[k] = v;
+    x[(long)b * d + k] = v;
+    s += v;
+  }
+  const float mean = block_sum_f(s, sh) / d;
+  float q = 0;
+  for (int k = threadIdx.x; k < d; k += 256) q += (row[k] - mean) * (row[k] - mean);
+  const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
+  for (int k8 = threadIdx.x; k8 < d / 8; k8 += 256) {
+    uint32_t pk[4];
+    for (int j = 0; j < 4; ++j) {
+      const int k = k8 * 8 + 2 * j;
+      pk[j] = pack2((row[k] - mean) * rstd * g[k] + bt[k], (row[k + 1] - mean) * rstd * g[k + 1] + bt[k + 1]);
+    }
+    *(uint32x4 *)&a_out[d_frag_index(b, k8 * 8, d)] = uint32x4{pk[0], pk[1], pk[2], pk[3]};
+  }
+}
+
+void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
+                    const float *g, const float *b, bf16_t *a_out, int B, int d) {
+  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(256), d * sizeof(float), s, partial, split, B_pad, bias, x, g, b,
+                     a_out, d);
+}
+
+// ------------------------------------------------------------------ decode attention over the paged KV cache
+// One workgroup (4 waves) per (row, head, split).  Wave w takes 32-key blocks
+// first + w, first + w + 4, ...; each block is 2 K tiles (QK^T: 2 * DH/32
+// MFMAs, q replicated over the 16 MFMA columns) and one V block (DH/16 MFMAs).
+// Online softmax per wave in fp32; the four waves (and, with splits > 1, the
+// workgroups of one head) are merged with the usual max / sum rescaling.
+template <int DH>
+__global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
+  constexpr int QC = DH / 32, VM = DH / 16;
+  __shared__ float sm_m[4], sm_l[4];
+  __shared__ float sm_o[4][DH];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4;
+  const int H = a.kv.H, b = blockIdx.x / H, h = blockIdx.x % H, d = H * DH;
+  const int j0 = a.start[b], t = a.t;
+  const int blk_lo = j0 >> 5, blk_hi = (t >> 5) + 1;  // blocks [blk_lo, blk_hi)
+  const int nblk = blk_hi - blk_lo;
+  const int per = (nblk + a.splits - 1) / a.splits;
+  const int my_lo = blk_lo + (int)blockIdx.y * per;
+  const int my_hi = min(my_lo + per, blk_hi);
+  const int bpp = a.kv.page_tokens >> 5;  // blocks per page
+  const int32_t *bt_row = a.bt_layer + (long)b * a.kv.max_pages;
+  const float scale = 1.0f / sqrtf((float)DH);
+
+  bf16x8 qf[QC];
+#pragma unroll
+  for (int c = 0; c < QC; ++c)
+    qf[c] = *(const bf16x8 *)&a.q[(long)b * d + h * DH + 32 * c + 8 * grp];
+
+  floatx4 O[VM];
+#pragma unroll
+  for (int m = 0; m < VM; ++m) O[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -1.0e30f, l_run = 0.f;  // l_run: this lane group's share of the denominator
+
+  for (int blk = my_lo + wave; blk < my_hi; blk += 4) {
+    const int page = bt_row[blk / bpp];
+    const bf16x8 *kp = (const bf16x8 *)(a.pool + (long)page * a.kv.page_elems + (long)h * (a.kv.page_tokens * DH * 2) +
+                                        (long)(blk % bpp) * (64 * DH)) + lane;
+    bf16x8 kf[2][QC], vf[VM];
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+      for (int c = 0; c < QC; ++c) kf[tl][c] = kp[(tl * QC + c) * 64];
+#pragma unroll
+    for (int m = 0; m < VM; ++m) vf[m] = kp[4 * DH + m * 64];
+
+    floatx4 S[2];
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+      S[tl] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < QC; ++c) S[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tl][c], qf[c], S[tl], 0, 0, 0);
+    }
+    // S[tl][i] = q . k of key  blk*32 + 16*tl + 4*grp + i
+    float sv[8];
+    bool ok[8];
+    float bm = -1.0e30f;
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = blk * 32 + 16 * tl + 4 * grp + i;
+        ok[tl * 4 + i] = (key >= j0) && (key <= t);
+        sv[tl * 4 + i] = S[tl][i] * scale;
+        if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
+      }
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    const float m_new = fmaxf(m_run, bm);
+    const float alpha = __expf(m_run - m_new);
+    float p[8], ps = 0.f;
+    uint32_t pk[4];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p[j] = ok[j] ? __expf(sv[j] - m_new) : 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      pk[j] = pack2(p[2 * j], p[2 * j + 1]);
+      ps += bf2f(pk[j] & 0xffffu) + bf2f(pk[j] >> 16);  // the denominator uses the rounded weights
+    }
+    l_run = l_run * alpha + ps;
+    m_run = m_new;
+    const uint32x4 pku = uint32x4{pk[0], pk[1], pk[2], pk[3]};
+    const bf16x8 pv = __builtin_bit_cast(bf16x8, pku);
+#pragma unroll
+    for (int m = 0; m < VM; ++m) {
+      O[m] *= alpha;
+      O[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[m], pv, O[m], 0, 0, 0);
+    }
+  }
+  // O[m][i] = sum_key p * v[key][16*m + 4*grp + i]   (same in all 16 columns)
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (lane == 0) { sm_m[wave] = m_run; sm_l[wave] = l_run; }
+  if ((lane & 15) == 0) {
+#pragma unroll
+    for (int m = 0; m < VM; ++m)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sm_o[wave][16 * m + 4 * grp + i] = O[m][i];
+  }
+  __syncthreads();
+  if (threadIdx.x < DH) {
+    const int e = threadIdx.x;
+    float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+    float num = 0.f, den = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float f = __expf(sm_m[w] - M);
+      num += f * sm_o[w][e];
+      den += f * sm_l[w];
+    }
+    if (a.splits == 1) {
+      const float r = den > 0.f ? num / den : 0.f;
+      a.o[d_frag_index(b, h * DH + e, d)] = (bf16_t)f2bf(r);
+    } else {
+      float *pp = a.part + ((long)blockIdx.y * gridDim.x + blockIdx.x) * (DH + 2);
+      pp[e] = num;
+      if (e == 0) { pp[DH] = M; pp[DH + 1] = den; }
+    }
+  }
+}
+
+template <int DH>
+__global__ void k_attn_merge(AttnArgs a) {
+  const int H = a.kv.H, b = blockIdx.x / H, h = blockIdx.x % H, d = H * DH, e = threadIdx.x;
+  float M = -1.0e30f;
+  for (int s = 0; s < a.splits; ++s) M = fmaxf(M, a.part[((long)s * gridDim.x + blockIdx.x) * (DH + 2) + DH]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < a.splits; ++s) {
+    const float *pp = a.part + ((long)s * gridDim.x + blockIdx.x) * (DH + 2);
+    const float f = __expf(pp[DH] - M);
+    num += f * pp[e];
+    den += f * pp[DH + 1];
+  }
+  a.o[d_frag_index(b, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
+}
+
+void bf16_attention(hipStream_t s, const AttnArgs &a) {
+  const dim3 grid(a.B * a.kv.H, a.splits);
+  if (a.kv.dh == 64) {
+    hipLaunchKernelGGL(k_attention<64>, grid, dim3(256), 0, s, a);
+    if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<64>, dim3(a.B * a.kv.H), dim3(64), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(k_attention<128>, grid, dim3(256), 0, s, a);
+    if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<128>, dim3(a.B * a.kv.H), dim3(128), 0, s, a);
+  }
+}
+
+// ------------------------------------------------------------------ argmax over workgroup partials
+__global__ void k_argmax_final(const float *pmax, const int32_t *pidx, int groups, int B_pad, int32_t *tokens) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  const int b = blockIdx.x;
+  float best = -3.0e38f;
+  int bi = 0x7fffffff;
+  for (int g = threadIdx.x; g < groups; g += 256) {
+    const float v = pmax[(long)g * B_pad + b];
+    const int i = pidx[(long)g * B_pad + b];
+    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  }
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      const float ov = sv[threadIdx.x + s];
+      const int oi = si[threadIdx.x + s];
+      if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) { sv[threadIdx.x] = ov; si[threadIdx.x] = oi; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) tokens[b] = si[0];
+}
+void bf16_argmax_final(hipStream_t s, const float *pmax, const int32_t *pidx, int groups, int B_pad, int32_t *tokens,
+                       int B) {
+  hipLaunchKernelGGL(k_argmax_final, dim3(B), dim3(256), 0, s, pmax, pidx, groups, B_pad, tokens);
+}
+
+// ------------------------------------------------------------------ weight preparation
+template <typename T>
+__device__ inline float src_to_f(const T *p, long i);
+template <>
+__device__ inline float src_to_f<float>(const float *p, long i) { return p[i]; }
+template <>
+__device__ inline float src_to_f<bf16_t>(const bf16_t *p, long i) { return bf2f(p[i]); }
+
+// one thread per 8-element lane slot of the destination
+template <typename T>
+__global__ void k_prep_frag(const T *src, bf16_t *dst, long N, long K, long N_pad) {
+  const long slot = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long Kf = K >> 5;
+  if (slot >= (N_pad >> 4) * Kf * 64) return;
+  const int lane = slot & 63;
+  const long frag = slot >> 6, kf = frag % Kf, nt = frag / Kf;
+  const long row = nt * 16 + (lane & 15), col = kf * 32 + (lane >> 4) * 8;
+  uint32_t pk[4] = {0, 0, 0, 0};
+  if (row < N)
+    for (int j = 0; j < 4; ++j) pk[j] = pack2(src_to_f<T>(src, row * K + col + 2 * j), src_to_f<T>(src, row * K + col + 2 * j + 1));
+  *(uint32x4 *)&dst[slot * 8] = uint32x4{pk[0], pk[1], pk[2], pk[3]};
+}
+template <typename T>
+__global__ void k_prep_rm(const T *src, bf16_t *dst, long n) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = (bf16_t)f2bf(src_to_f<T>(src, i));
+}
+template <typename T>
+__global__ void k_prep_f32(const T *src, float *dst, long n) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src_to_f<T>(src, i);
+}
+void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long N, long K, long N_pad) {
+  const long slots = (N_pad / 16) * (K / 32) * 64;
+  const dim3 grid((unsigned)((slots + 255) / 256));
+  if (src_is_bf16) hipLaunchKernelGGL(k_prep_frag<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, N, K, N_pad);
+  else hipLaunchKernelGGL(k_prep_frag<float>, grid, dim3(256), 0, s, (const float *)src, dst, N, K, N_pad);
+}
+void prep_matrix_rm_bf16(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long n) {
+  const dim3 grid((unsigned)((n + 255) / 256));
+  if (src_is_bf16) hipLaunchKernelGGL(k_prep_rm<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, n);
+  else hipLaunchKernelGGL(k_prep_rm<float>, grid, dim3(256), 0, s, (const float *)src, dst, n);
+}
+void prep_to_f32(hipStream_t s, const void *src, int src_is_bf16, float *dst, long n) {
+  const dim3 grid((unsigned)((n + 255) / 256));
+  if (src_is_bf16) hipLaunchKernelGGL(k_prep_f32<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, n);
+  else hipLaunchKernelGGL(k_prep_f32<float>, grid, dim3(256), 0, s, (const float *)src, dst, n);
+}
+
+// ------------------------------------------------------------------ KV debug hooks (bf16 pages)
+__global__ void k_kv_load_bf16(const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer, int cols,
+                               KvGeom g) {
+  const int b = blockIdx.y, j = blockIdx.x, d = g.H * g.dh;
+  const int page = bt_layer[(long)b * g.max_pages + j / g.page_tokens];
+  bf16_t *pg = pool + (long)page * g.page_elems;
+  const int tt = j % g.page_tokens;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    const int h = k / g.dh, e = k % g.dh;
+    pg[kv_k_off(h, tt, e, g)] = (bf16_t)f2bf(K ? K[((long)b * cols + j) * d + k] : 0.f);
+    pg[kv_v_off(h, tt, e, g)] = (bf16_t)f2bf(V ? V[((long)b * cols + j) * d + k] : 0.f);
+  }
+}
+__global__ void k_kv_read_bf16(const bf16_t *pool, const int32_t *bt_row, float *K, float *V, KvGeom g) {
+  const int j = blockIdx.x, d = g.H * g.dh;
+  const bf16_t *pg = pool + (long)bt_row[j / g.page_tokens] * g.page_elems;
+  const int tt = j % g.page_tokens;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    const int h = k / g.dh, e = k % g.dh;
+    K[(long)j * d + k] = bf2f(pg[kv_k_off(h, tt, e, g)]);
+    V[(long)j * d + k] = bf2f(pg[kv_v_off(h, tt, e, g)]);
+  }
+}
+void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer, int cols,
+                  int B, KvGeom g) {
+  if (cols > 0) hipLaunchKernelGGL(k_kv_load_bf16, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, cols, g);
+}
+void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g) {
+  if (len > 0) hipLaunchKernelGGL(k_kv_read_bf16, dim3(len), dim3(256), 0, s, pool, bt_row, K, V, g);
+}
+
+}  // namespace skd

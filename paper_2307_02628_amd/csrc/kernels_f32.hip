@@ -1,0 +1,187 @@
+// fp32 debug path: small, straightforward kernels (no MFMA, no tiling) whose
+// only job is to be an easily-audited GPU implementation of the decode step
+// for the tight-tolerance parity build.  Not tuned.
+#include "skd_kernels.h"
+
+namespace skd {
+
+__device__ inline float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+// sum over a 256-thread workgroup; `sh` holds >= 4 floats; result to all threads
+__device__ inline float block_sum(float v, float *sh) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = 0;
+  for (unsigned w = 0; w < (blockDim.x >> 6); ++w) r += sh[w];
+  return r;
+}
+
+__global__ void k_f32_embed(float *x, const float *tok_emb, const float *pos_emb, const int32_t *tokens,
+                            const int32_t *start, int t, int d, int V) {
+  const int b = blockIdx.x;
+  int tok = tokens[b];
+  tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+  int pos = t - start[b];  // real tokens before this column
+  if (pos < 0) pos = 0;    // padding column: never read later
+  for (int k = threadIdx.x; k < d; k += blockDim.x) x[(long)b * d + k] = tok_emb[(long)tok * d + k] + pos_emb[(long)pos * d + k];
+}
+
+__global__ void k_f32_layernorm(const float *x, const float *g, const float *bt, float *out, int d) {
+  __shared__ float sh[4];
+  const float *xr = x + (long)blockIdx.x * d;
+  float s = 0;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) s += xr[k];
+  const float mean = block_sum(s, sh) / d;
+  float v = 0;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) v += (xr[k] - mean) * (xr[k] - mean);
+  const float rstd = 1.0f / sqrtf(block_sum(v, sh) / d + 1e-5f);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) out[(long)blockIdx.x * d + k] = (xr[k] - mean) * rstd * g[k] + bt[k];
+}
+
+// one wave per output element (b, n): lanes stride over k
+__global__ void k_f32_linear(const float *W, const float *bias, const float *in, float *out, int K, int N, int relu,
+                             int accumulate) {
+  const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int b = blockIdx.y;
+  if (n >= N) return;
+  const float *w = W + (long)n * K, *a = in + (long)b * K;
+  float acc = 0;
+  for (int k = threadIdx.x & 63; k < K; k += 64) acc += w[k] * a[k];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) {
+    float v = acc + (bias ? bias[n] : 0.f);
+    if (relu) v = fmaxf(v, 0.f);
+    float *o = out + (long)b * N + n;
+    *o = accumulate ? *o + v : v;
+  }
+}
+
+__device__ inline long f32_kv_off(const int32_t *bt_row, int pos, int which, const KvGeom &g) {
+  const int page = bt_row[pos / g.page_tokens];
+  return (long)page * g.page_elems + ((long)which * g.page_tokens + pos % g.page_tokens) * (g.H * g.dh);
+}
+
+__global__ void k_f32_kv_write(const float *qkv, float *pool, const int32_t *bt_layer, int t, KvGeom g) {
+  const int b = blockIdx.x, d = g.H * g.dh;
+  const int32_t *bt_row = bt_layer + (long)b * g.max_pages;
+  float *Kd = pool + f32_kv_off(bt_row, t, 0, g), *Vd = pool + f32_kv_off(bt_row, t, 1, g);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    Kd[k] = qkv[(long)b * 3 * d + d + k];
+    Vd[k] = qkv[(long)b * 3 * d + 2 * d + k];
+  }
+}
+
+// one 64-lane workgroup per (b, h); scores kept in a global scratch row
+__global__ void k_f32_attention(const float *qkv, const float *pool, const int32_t *bt_layer, const int32_t *start,
+                                int t, float *o, float *scores, int score_stride, KvGeom g) {
+  const int b = blockIdx.x / g.H, h = blockIdx.x % g.H, d = g.H * g.dh, lane = threadIdx.x;
+  const int32_t *bt_row = bt_layer + (long)b * g.max_pages;
+  const float *q = qkv + (long)b * 3 * d + h * g.dh;
+  float *sc = scores + (long)blockIdx.x * score_stride;
+  const int j0 = start[b];
+  const float inv = 1.0f / sqrtf((float)g.dh);
+  float mx = -3.0e38f;
+  for (int j = j0 + lane; j <= t; j += 64) {
+    const float *kr = pool + f32_kv_off(bt_row, j, 0, g) + h * g.dh;
+    float s = 0;
+    for (int e = 0; e < g.dh; ++e) s += q[e] * kr[e];
+    s *= inv;
+    sc[j] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = wave_max(mx);
+  float den = 0;
+  for (int j = j0 + lane; j <= t; j += 64) {
+    const float p = expf(sc[j] - mx);
+    sc[j] = p;
+    den += p;
+  }
+  den = wave_sum(den);
+  __syncthreads();  // scores written by other lanes are read below
+  for (int e = lane; e < g.dh; e += 64) {
+    float acc = 0;
+    for (int j = j0; j <= t; ++j) acc += sc[j] * pool[f32_kv_off(bt_row, j, 1, g) + h * g.dh + e];
+    o[(long)b * d + h * g.dh + e] = (j0 <= t) ? acc / den : 0.f;
+  }
+}
+
+__global__ void k_f32_argmax(const float *logits, int32_t *tokens, int V) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  const float *z = logits + (long)blockIdx.x * V;
+  float best = -3.0e38f;
+  int bi = 0x7fffffff;
+  for (int v = threadIdx.x; v < V; v += blockDim.x)
+    if (z[v] > best) { best = z[v]; bi = v; }  // ascending v per thread: first maximum kept
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int s = blockDim.x / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      const float ov = sv[threadIdx.x + s];
+      const int oi = si[threadIdx.x + s];
+      if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) { sv[threadIdx.x] = ov; si[threadIdx.x] = oi; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) tokens[blockIdx.x] = si[0];
+}
+
+void f32_embed(hipStream_t s, float *x, const float *tok_emb, const float *pos_emb, const int32_t *tokens,
+               const int32_t *start, int t, int B, int d, int V) {
+  hipLaunchKernelGGL(k_f32_embed, dim3(B), dim3(256), 0, s, x, tok_emb, pos_emb, tokens, start, t, d, V);
+}
+void f32_layernorm(hipStream_t s, const float *x, const float *g, const float *b, float *out, int B, int d) {
+  hipLaunchKernelGGL(k_f32_layernorm, dim3(B), dim3(256), 0, s, x, g, b, out, d);
+}
+void f32_linear(hipStream_t s, const float *W, const float *bias, const float *in, float *out, int B, int K, int N,
+                int relu, int accumulate) {
+  hipLaunchKernelGGL(k_f32_linear, dim3((N + 3) / 4, B), dim3(256), 0, s, W, bias, in, out, K, N, relu, accumulate);
+}
+void f32_kv_write(hipStream_t s, const float *qkv, float *pool, const int32_t *bt_layer, int t, int B, KvGeom g) {
+  hipLaunchKernelGGL(k_f32_kv_write, dim3(B), dim3(256), 0, s, qkv, pool, bt_layer, t, g);
+}
+void f32_attention(hipStream_t s, const float *qkv, const float *pool, const int32_t *bt_layer, const int32_t *start,
+                   int t, float *o, float *scores, int score_stride, int B, KvGeom g) {
+  hipLaunchKernelGGL(k_f32_attention, dim3(B * g.H), dim3(64), 0, s, qkv, pool, bt_layer, start, t, o, scores,
+                     score_stride, g);
+}
+void f32_argmax(hipStream_t s, const float *logits, int32_t *tokens, int B, int V) {
+  hipLaunchKernelGGL(k_f32_argmax, dim3(B), dim3(256), 0, s, logits, tokens, V);
+}
+
+// ------------------------------------------------------------------ KV debug hooks (fp32 pages)
+__global__ void k_kv_load_f32(const float *K, const float *V, float *pool, const int32_t *bt_layer, int cols,
+                              KvGeom g) {
+  const int b = blockIdx.y, j = blockIdx.x, d = g.H * g.dh;
+  const int32_t *bt_row = bt_layer + (long)b * g.max_pages;
+  float *Kd = pool + f32_kv_off(bt_row, j, 0, g), *Vd = pool + f32_kv_off(bt_row, j, 1, g);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    Kd[k] = K ? K[((long)b * cols + j) * d + k] : 0.f;
+    Vd[k] = V ? V[((long)b * cols + j) * d + k] : 0.f;
+  }
+}
+__global__ void k_kv_read_f32(const float *pool, const int32_t *bt_row, float *K, float *V, KvGeom g) {
+  const int j = blockIdx.x, d = g.H * g.dh;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    K[(long)j * d + k] = pool[f32_kv_off(bt_row, j, 0, g) + k];
+    V[(long)j * d + k] = pool[f32_kv_off(bt_row, j, 1, g) + k];
+  }
+}
+void kv_load_f32(hipStream_t s, const float *K, const float *V, float *pool, const int32_t *bt_layer, int cols, int B,
+                 KvGeom g) {
+  if (cols > 0) hipLaunchKernelGGL(k_kv_load_f32, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, cols, g);
+}
+void kv_read_f32(hipStream_t s, const float *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g) {
+  if (len > 0) hipLaunchKernelGGL(k_kv_read_f32, dim3(len), dim3(256), 0, s, pool, bt_row, K, V, g);
+}
+
+}  // namespace skd

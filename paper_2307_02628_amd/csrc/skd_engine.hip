@@ -1,0 +1,624 @@
+// Host engine behind the C ABI of include/skd.h: configuration checks, weight
+// upload, the layer-sparse paged KV cache and the skip-aware layer loop that
+// launches kernels for the active layers only (Sections 2.1-2.4).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/skd.h"
+#include "skd_kernels.h"
+
+using namespace skd;
+
+static thread_local int g_last_hip = 0;
+extern "C" int skd_last_hip_error(void) { return g_last_hip; }
+
+#define HIPCHECK(expr)                         \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) {                    \
+      g_last_hip = (int)e_;                    \
+      return e_ == hipErrorOutOfMemory ? SKD_ERR_NOMEM : SKD_ERR_HIP; \
+    }                                          \
+  } while (0)
+#define SKDCHECK(expr)       \
+  do {                       \
+    int r_ = (expr);         \
+    if (r_ < 0) return r_;   \
+  } while (0)
+
+namespace {
+
+struct LayerW {
+  // matrices: fp32 row-major (debug path) or bf16 fragment-major (production path)
+  void *wqkv = nullptr, *wo = nullptr, *w1 = nullptr, *w2 = nullptr;
+  float *ln1_g = nullptr, *ln1_b = nullptr, *bqkv = nullptr, *bo = nullptr;
+  float *ln2_g = nullptr, *ln2_b = nullptr, *b1 = nullptr, *b2 = nullptr;
+};
+
+struct GemmPlan {
+  int R = 1, split = 1;
+};
+
+}  // namespace
+
+struct skd_state {
+  skd_config cfg{};
+  hipStream_t stream = nullptr;
+  int B_pad = 0, dh = 0;
+  bool bf16 = true;
+  std::vector<void *> allocs;
+  // weights
+  std::vector<LayerW> lw;
+  void *tok_emb = nullptr;  // row-major (gather)
+  void *pos_emb = nullptr;  // row-major
+  void *head = nullptr;     // LM head: fp32 row-major or bf16 fragment-major
+  float *lnf_g = nullptr, *lnf_b = nullptr;
+  // KV cache
+  KvGeom geom{};
+  void *pool = nullptr;
+  int32_t *bt_dev = nullptr;       // [L][B][max_pages]
+  std::vector<int32_t> bt_host;
+  std::vector<int> kv_len, kv_cap; // columns held / columns reserved, per layer
+  int64_t pages_reserved = 0, pages_dense = 0;
+  // per-step device buffers
+  int32_t *tok_dev = nullptr;      // [B] input column
+  int32_t *prompt_dev = nullptr;   // [P][B]
+  int32_t *start_dev = nullptr;    // [B] first real column
+  int32_t *argmax_dev = nullptr;   // [B]
+  float *x = nullptr;              // residual stream fp32 [B_pad][d]
+  void *a = nullptr;               // LayerNorm output
+  void *q = nullptr;               // bf16: q [B_pad][d]; fp32: qkv [B][3d]
+  void *o = nullptr;               // attention output
+  void *u = nullptr;               // FFN hidden
+  float *partial = nullptr;        // bf16: split-K partials
+  float *attn_part = nullptr;      // bf16: split-KV partials; fp32: score scratch
+  float *logits_dev = nullptr;     // [B][V] (fp32 path always; bf16 path when asked)
+  float *pmax = nullptr;
+  int32_t *pidx = nullptr;
+  // plans (bf16)
+  GemmPlan p_qkv, p_out, p_ffn1, p_ffn2, p_head;
+  int max_split = 1, attn_splits = 1;
+  // sequencing
+  bool prefilled = false, have_hidden = false, have_argmax = false;
+  int steps_done = 0;
+  std::vector<int32_t> layers_tmp;
+};
+
+namespace {
+
+template <typename T>
+int dev_alloc(skd_state *st, T **out, size_t count) {
+  void *p = nullptr;
+  HIPCHECK(hipMalloc(&p, std::max<size_t>(count * sizeof(T), 256)));
+  st->allocs.push_back(p);
+  *out = (T *)p;
+  return SKD_OK;
+}
+
+int env_int(const char *name, int dflt) {
+  const char *v = getenv(name);
+  return v && *v ? atoi(v) : dflt;
+}
+
+int check_config(const skd_config &c) {
+  if (c.L < 1 || c.d_model < 1 || c.n_heads < 1 || c.ffn < 1 || c.vocab < 1 || c.max_pos < 1) return SKD_ERR_SHAPE;
+  if (c.d_model % c.n_heads) return SKD_ERR_SHAPE;
+  if (c.batch < 1 || c.prompt_size < 1 || c.sequence_length <= c.prompt_size) return SKD_ERR_SHAPE;
+  if (c.max_pos < c.sequence_length) return SKD_ERR_SHAPE;
+  if (c.n_min < 1 || c.n_min > c.n_max || c.n_max > c.L) return SKD_ERR_SHAPE;
+  if (c.warmup < 0 || c.warmup > c.n_min) return SKD_ERR_SHAPE;
+  if (c.page_tokens < 0 || c.page_tokens % 32) return SKD_ERR_SHAPE;
+  if (c.dtype != SKD_BF16 && c.dtype != SKD_FP32) return SKD_ERR_SHAPE;
+  if (c.io_on_device != 0 && c.io_on_device != 1) return SKD_ERR_SHAPE;
+  if (c.dtype == SKD_BF16) {
+    const int dh = c.d_model / c.n_heads;
+    if (dh != 64 && dh != 128) return SKD_ERR_SHAPE;
+    if (c.d_model % 32 || c.ffn % 32) return SKD_ERR_SHAPE;
+    if (c.batch > 128) return SKD_ERR_SHAPE;
+  }
+  return SKD_OK;
+}
+
+// Upload one tensor (host or device, fp32 or bf16) into a device staging area.
+int stage(skd_state *st, const skd_weights &w, const void *src, size_t n, void *staging, const void **dev_src) {
+  if (!src) return SKD_ERR_NULL;
+  if (w.location == SKD_DEVICE) {
+    *dev_src = src;
+    return SKD_OK;
+  }
+  const size_t bytes = n * (w.elem == SKD_W_BF16 ? 2 : 4);
+  HIPCHECK(hipMemcpyAsync(staging, src, bytes, hipMemcpyHostToDevice, st->stream));
+  HIPCHECK(hipStreamSynchronize(st->stream));  // the staging area is reused by the next tensor
+  *dev_src = staging;
+  return SKD_OK;
+}
+
+int upload_vec(skd_state *st, const skd_weights &w, const void *src, size_t n, void *staging, float **out) {
+  const void *dsrc = nullptr;
+  SKDCHECK(stage(st, w, src, n, staging, &dsrc));
+  SKDCHECK(dev_alloc(st, out, n));
+  prep_to_f32(st->stream, dsrc, w.elem == SKD_W_BF16, *out, (long)n);
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
+}
+
+// matrix [N][K]: fp32 path -> fp32 row-major; bf16 path -> fragment-major (frag) or row-major bf16
+int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, long K, void *staging, bool frag,
+               void **out) {
+  const void *dsrc = nullptr;
+  SKDCHECK(stage(st, w, src, (size_t)N * K, staging, &dsrc));
+  if (!st->bf16) {
+    float *p = nullptr;
+    SKDCHECK(dev_alloc(st, &p, (size_t)N * K));
+    prep_to_f32(st->stream, dsrc, w.elem == SKD_W_BF16, p, N * K);
+    *out = p;
+  } else if (frag) {
+    const long N_pad = (N + 63) / 64 * 64;  // whole 4-tile groups: the widest wave tile never leaves the buffer
+    bf16_t *p = nullptr;
+    SKDCHECK(dev_alloc(st, &p, (size_t)N_pad * K));
+    prep_matrix_frag(st->stream, dsrc, w.elem == SKD_W_BF16, p, N, K, N_pad);
+    *out = p;
+  } else {
+    bf16_t *p = nullptr;
+    SKDCHECK(dev_alloc(st, &p, (size_t)N * K));
+    prep_matrix_rm_bf16(st->stream, dsrc, w.elem == SKD_W_BF16, p, N * K);
+    *out = p;
+  }
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
+}
+
+GemmPlan plan_direct(int N, int B_pad) {  // whole K inside the workgroup
+  GemmPlan p;
+  const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
+  p.R = 1;
+  for (int R = rmax; R >= 1; R >>= 1)
+    if (bf16_gemm_groups(N, R) >= 256) { p.R = R; break; }
+  p.split = 1;
+  return p;
+}
+GemmPlan plan_split(int N, int K, int B_pad) {  // partial sums, reduced by the LayerNorm kernel
+  GemmPlan p;
+  const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
+  p.R = rmax;
+  while (p.R > 1 && N % (16 * p.R)) p.R >>= 1;
+  const int groups = bf16_gemm_groups(N, p.R);
+  const int Kf = K / 32;
+  int S = 1;
+  while (S < 16 && groups * S < 512 && Kf / (4 * S * 2) >= 4) S *= 2;
+  p.split = S;
+  return p;
+}
+
+int build_kv(skd_state *st) {
+  const skd_config &c = st->cfg;
+  const int pt = c.page_tokens ? c.page_tokens : 64;
+  KvGeom &g = st->geom;
+  g.page_tokens = pt;
+  g.max_pages = (c.sequence_length + pt - 1) / pt;
+  g.H = c.n_heads;
+  g.dh = st->dh;
+  g.page_elems = 2L * pt * c.d_model;
+  // Static policy: the columns at which each layer runs are known before
+  // generation starts, so each layer reserves exactly what it will hold.
+  st->kv_cap.assign(c.L, c.prompt_size);
+  std::vector<int32_t> act(c.L);
+  for (int t = c.prompt_size; t < c.sequence_length; ++t) {
+    const int n = skd_active_layers(t, &c, act.data());
+    if (n < 0) return n;
+    for (int i = 0; i < n; ++i) {
+      if (st->kv_cap[act[i]] != t) return SKD_ERR_SCHEDULE;  // a layer re-entered: its cache would have a hole
+      st->kv_cap[act[i]] = t + 1;
+    }
+  }
+  st->bt_host.assign((size_t)c.L * c.batch * g.max_pages, -1);
+  int64_t next = 0;
+  for (int l = 0; l < c.L; ++l) {
+    const int np = (st->kv_cap[l] + pt - 1) / pt;
+    for (int b = 0; b < c.batch; ++b)
+      for (int p = 0; p < np; ++p) st->bt_host[((size_t)l * c.batch + b) * g.max_pages + p] = (int32_t)next++;
+  }
+  if (next > 0x7fffffffLL) return SKD_ERR_NOMEM;
+  st->pages_reserved = next;
+  st->pages_dense = (int64_t)c.L * c.batch * g.max_pages;
+  const size_t esz = st->bf16 ? 2 : 4;
+  const size_t bytes = (size_t)next * g.page_elems * esz;
+  void *pool = nullptr;
+  HIPCHECK(hipMalloc(&pool, std::max<size_t>(bytes, 256)));
+  st->allocs.push_back(pool);
+  st->pool = pool;
+  // unwritten slots must hold finite values: a masked key still meets its V in the MFMA
+  HIPCHECK(hipMemsetAsync(pool, 0, bytes, st->stream));
+  SKDCHECK(dev_alloc(st, &st->bt_dev, st->bt_host.size()));
+  HIPCHECK(hipMemcpyAsync(st->bt_dev, st->bt_host.data(), st->bt_host.size() * sizeof(int32_t), hipMemcpyHostToDevice,
+                          st->stream));
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  st->kv_len.assign(c.L, 0);
+  return SKD_OK;
+}
+
+const int32_t *bt_layer(const skd_state *st, int l) {
+  return st->bt_dev + (size_t)l * st->cfg.batch * st->geom.max_pages;
+}
+
+// One column (all B rows at position t) through the given ascending layer list.
+int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *layers, int n) {
+  const skd_config &c = st->cfg;
+  const int B = c.batch, d = c.d_model, f = c.ffn;
+  hipStream_t s = st->stream;
+  for (int i = 0; i < n; ++i) {
+    const int l = layers[i];
+    if (l < 0 || l >= c.L || (i && layers[i - 1] >= l)) return SKD_ERR_SCHEDULE;
+    if (st->kv_len[l] != t) return SKD_ERR_ORDER;  // every earlier key of an active layer must exist
+    if (t >= st->kv_cap[l]) return SKD_ERR_NOMEM;
+  }
+  if (!st->bf16) {
+    float *a = (float *)st->a, *qkv = (float *)st->q, *o = (float *)st->o, *u = (float *)st->u;
+    f32_embed(s, st->x, (const float *)st->tok_emb, (const float *)st->pos_emb, tokens_dev, st->start_dev, t, B, d,
+              c.vocab);
+    for (int i = 0; i < n; ++i) {
+      const LayerW &w = st->lw[layers[i]];
+      f32_layernorm(s, st->x, w.ln1_g, w.ln1_b, a, B, d);
+      f32_linear(s, (const float *)w.wqkv, w.bqkv, a, qkv, B, d, 3 * d, 0, 0);
+      f32_kv_write(s, qkv, (float *)st->pool, bt_layer(st, layers[i]), t, B, st->geom);
+      f32_attention(s, qkv, (const float *)st->pool, bt_layer(st, layers[i]), st->start_dev, t, o, st->attn_part,
+                    c.sequence_length, B, st->geom);
+      f32_linear(s, (const float *)w.wo, w.bo, o, st->x, B, d, d, 0, 1);
+      f32_layernorm(s, st->x, w.ln2_g, w.ln2_b, a, B, d);
+      f32_linear(s, (const float *)w.w1, w.b1, a, u, B, d, f, 1, 0);
+      f32_linear(s, (const float *)w.w2, w.b2, u, st->x, B, f, d, 0, 1);
+      st->kv_len[layers[i]] = t + 1;
+    }
+  } else {
+    bf16_t *a = (bf16_t *)st->a, *q = (bf16_t *)st->q, *o = (bf16_t *)st->o, *u = (bf16_t *)st->u;
+    const LayerW &w0 = st->lw[layers[0]];
+    bf16_embed_ln(s, tokens_dev, st->start_dev, t, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, w0.ln1_g,
+                  w0.ln1_b, st->x, a, B, d, c.vocab);
+    for (int i = 0; i < n; ++i) {
+      const int l = layers[i];
+      const LayerW &w = st->lw[l];
+      GemmArgs ga{};
+      ga.B = B; ga.B_pad = st->B_pad; ga.kv = st->geom; ga.t = t; ga.d = d;
+      // q, k, v projection; k and v go straight into this layer's page slot for column t
+      ga.W = (const bf16_t *)w.wqkv; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
+      ga.q_out = q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
+      bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R);
+      AttnArgs aa{};
+      aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
+      aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
+      bf16_attention(s, aa);
+      // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
+      ga.W = (const bf16_t *)w.wo; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
+      bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R);
+      bf16_reduce_ln(s, st->partial, st->p_out.split, st->B_pad, w.bo, st->x, w.ln2_g, w.ln2_b, a, B, d);
+      ga.W = (const bf16_t *)w.w1; ga.A = a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.split = 1; ga.act_out = u;
+      bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R);
+      ga.W = (const bf16_t *)w.w2; ga.A = u; ga.N = d; ga.K = f; ga.split = st->p_ffn2.split;
+      bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R);
+      // the reducer of the last sub-block already applies the next LayerNorm:
+      // LayerNorm 1 of the next ACTIVE layer, or the final LayerNorm
+      const float *ng = (i + 1 < n) ? st->lw[layers[i + 1]].ln1_g : st->lnf_g;
+      const float *nb = (i + 1 < n) ? st->lw[layers[i + 1]].ln1_b : st->lnf_b;
+      bf16_reduce_ln(s, st->partial, st->p_ffn2.split, st->B_pad, w.b2, st->x, ng, nb, a, B, d);
+      st->kv_len[l] = t + 1;
+    }
+  }
+  HIPCHECK(hipGetLastError());
+  st->have_hidden = true;
+  st->have_argmax = false;
+  return SKD_OK;
+}
+
+}  // namespace
+
+extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip_stream, skd_state **out) {
+  if (!cfg || !w || !out) return SKD_ERR_NULL;
+  *out = nullptr;
+  SKDCHECK(check_config(*cfg));
+  if ((w->location != SKD_HOST && w->location != SKD_DEVICE) || (w->elem != SKD_W_FP32 && w->elem != SKD_W_BF16))
+    return SKD_ERR_SHAPE;
+  if (!w->tok_emb || !w->pos_emb || !w->lnf_g || !w->lnf_b || !w->ln1_g || !w->ln1_b || !w->wqkv || !w->bqkv ||
+      !w->wo || !w->bo || !w->ln2_g || !w->ln2_b || !w->w1 || !w->b1 || !w->w2 || !w->b2)
+    return SKD_ERR_NULL;
+  skd_state *st = new (std::nothrow) skd_state();
+  if (!st) return SKD_ERR_NOMEM;
+  auto fail = [&](int rc) {
+    skd_destroy(st);
+    return rc;
+  };
+  st->cfg = *cfg;
+  if (!st->cfg.page_tokens) st->cfg.page_tokens = 64;
+  st->stream = (hipStream_t)hip_stream;
+  st->bf16 = cfg->dtype == SKD_BF16;
+  st->dh = cfg->d_model / cfg->n_heads;
+  const skd_config &c = st->cfg;
+  const int B = c.batch, d = c.d_model, f = c.ffn, V = c.vocab, L = c.L;
+  st->B_pad = 16;
+  while (st->B_pad < B) st->B_pad *= 2;
+  st->layers_tmp.resize(L);
+
+  // ---- weights
+  const size_t esz = w->elem == SKD_W_BF16 ? 2 : 4;
+  size_t biggest = std::max({(size_t)V * d, (size_t)c.max_pos * d, (size_t)3 * d * d, (size_t)f * d});
+  void *staging = nullptr;
+  if (w->location == SKD_HOST) {
+    hipError_t e = hipMalloc(&staging, biggest * esz);
+    if (e != hipSuccess) { g_last_hip = (int)e; return fail(SKD_ERR_NOMEM); }
+  }
+  int rc = SKD_OK;
+  auto vec = [&](const void *src, size_t n, float **o) { if (rc == SKD_OK) rc = upload_vec(st, *w, src, n, staging, o); };
+  auto mat = [&](const void *src, long N, long K, bool frag, void **o) { if (rc == SKD_OK) rc = upload_mat(st, *w, src, N, K, staging, frag, o); };
+  mat(w->tok_emb, V, d, false, &st->tok_emb);
+  mat(w->pos_emb, c.max_pos, d, false, &st->pos_emb);
+  if (st->bf16 || w->lm_head) mat(w->lm_head ? w->lm_head : w->tok_emb, V, d, true, &st->head);
+  else st->head = st->tok_emb;
+  vec(w->lnf_g, d, &st->lnf_g);
+  vec(w->lnf_b, d, &st->lnf_b);
+  st->lw.resize(L);
+  for (int l = 0; l < L && rc == SKD_OK; ++l) {
+    LayerW &lw = st->lw[l];
+    vec(w->ln1_g[l], d, &lw.ln1_g); vec(w->ln1_b[l], d, &lw.ln1_b);
+    mat(w->wqkv[l], 3L * d, d, true, &lw.wqkv); vec(w->bqkv[l], 3 * (size_t)d, &lw.bqkv);
+    mat(w->wo[l], d, d, true, &lw.wo); vec(w->bo[l], d, &lw.bo);
+    vec(w->ln2_g[l], d, &lw.ln2_g); vec(w->ln2_b[l], d, &lw.ln2_b);
+    mat(w->w1[l], f, d, true, &lw.w1); vec(w->b1[l], f, &lw.b1);
+    mat(w->w2[l], d, f, true, &lw.w2); vec(w->b2[l], d, &lw.b2);
+  }
+  if (staging) (void)hipFree(staging);
+  if (rc != SKD_OK) return fail(rc);
+
+  // ---- KV cache
+  rc = build_kv(st);
+  if (rc != SKD_OK) return fail(rc);
+
+  // ---- workspaces
+  const int Bp = st->B_pad;
+  auto A = [&](auto **p, size_t n) { if (rc == SKD_OK) rc = dev_alloc(st, p, n); };
+  A(&st->tok_dev, B); A(&st->prompt_dev, (size_t)c.prompt_size * B); A(&st->start_dev, B); A(&st->argmax_dev, B);
+  A(&st->x, (size_t)Bp * d);
+  if (st->bf16) {
+    st->p_qkv = plan_direct(3 * d, Bp);
+    st->p_ffn1 = plan_direct(f, Bp);
+    st->p_head = plan_direct(V, Bp);
+    st->p_out = plan_split(d, d, Bp);
+    st->p_ffn2 = plan_split(d, f, Bp);
+    auto ov = [&](const char *name, int &v, int lo, int hi) { const int e = env_int(name, 0); if (e >= lo && e <= hi) v = e; };
+    ov("SKD_R_QKV", st->p_qkv.R, 1, 4); ov("SKD_R_FFN1", st->p_ffn1.R, 1, 4); ov("SKD_R_HEAD", st->p_head.R, 1, 4);
+    ov("SKD_R_OUT", st->p_out.R, 1, 4); ov("SKD_R_FFN2", st->p_ffn2.R, 1, 4);
+    ov("SKD_S_OUT", st->p_out.split, 1, 32); ov("SKD_S_FFN2", st->p_ffn2.split, 1, 32);
+    for (GemmPlan *p : {&st->p_qkv, &st->p_ffn1, &st->p_head, &st->p_out, &st->p_ffn2}) {
+      if (p->R == 3) p->R = 2;
+      if (Bp >= 128) p->R = 1; else if (Bp >= 64 && p->R > 2) p->R = 2;
+    }
+    st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
+    // split the key range of one head over several workgroups only when rows*heads alone cannot fill the chip
+    int splits = 1;
+    while (B * c.n_heads * splits < 512 && splits < 8) splits *= 2;
+    ov("SKD_ATTN_SPLITS", splits, 1, 16);
+    st->attn_splits = splits;
+    bf16_t *t16 = nullptr;
+    A(&t16, (size_t)Bp * d); st->a = t16; if (rc == SKD_OK) rc = hipMemsetAsync(st->a, 0, (size_t)Bp * d * 2, st->stream) == hipSuccess ? SKD_OK : SKD_ERR_HIP;
+    A(&t16, (size_t)Bp * d); st->q = t16;
+    A(&t16, (size_t)Bp * d); st->o = t16; if (rc == SKD_OK) rc = hipMemsetAsync(st->o, 0, (size_t)Bp * d * 2, st->stream) == hipSuccess ? SKD_OK : SKD_ERR_HIP;
+    A(&t16, (size_t)Bp * f); st->u = t16;
+    A(&st->partial, (size_t)st->max_split * Bp * d);
+    A(&st->attn_part, (size_t)st->attn_splits * B * c.n_heads * (st->dh + 2));
+    const int groups = bf16_gemm_groups(V, st->p_head.R);
+    A(&st->pmax, (size_t)groups * Bp); A(&st->pidx, (size_t)groups * Bp);
+    A(&st->logits_dev, (size_t)B * V);
+  } else {
+    float *t32 = nullptr;
+    A(&t32, (size_t)B * d); st->a = t32;
+    A(&t32, (size_t)B * 3 * d); st->q = t32;
+    A(&t32, (size_t)B * d); st->o = t32;
+    A(&t32, (size_t)B * f); st->u = t32;
+    A(&st->attn_part, (size_t)B * c.n_heads * c.sequence_length);
+    A(&st->logits_dev, (size_t)B * V);
+  }
+  if (rc != SKD_OK) return fail(rc);
+  if (hipStreamSynchronize(st->stream) != hipSuccess) return fail(SKD_ERR_HIP);
+  *out = st;
+  return SKD_OK;
+}
+
+extern "C" void skd_destroy(skd_state *st) {
+  if (!st) return;
+  (void)hipStreamSynchronize(st->stream);
+  for (void *p : st->allocs) (void)hipFree(p);
+  delete st;
+}
+
+extern "C" int skd_prefill(skd_state *st, const int32_t *tokens, const uint8_t *attn_mask) {
+  if (!st || !tokens) return SKD_ERR_NULL;
+  const skd_config &c = st->cfg;
+  const int B = c.batch, P = c.prompt_size;
+  std::vector<int32_t> start(B, 0);
+  if (attn_mask) {
+    for (int b = 0; b < B; ++b) {
+      int j = 0;
+      while (j < P && attn_mask[(size_t)b * P + j] == 0) ++j;
+      if (j == P) return SKD_ERR_SHAPE;  // a row needs at least one real token
+      start[b] = j;
+      for (; j < P; ++j)
+        if (attn_mask[(size_t)b * P + j] == 0) return SKD_ERR_SHAPE;  // only left padding
+    }
+  }
+  const int32_t *cols = nullptr;
+  if (c.io_on_device) {
+    cols = tokens;
+  } else {
+    std::vector<int32_t> tr((size_t)P * B);
+    for (int b = 0; b < B; ++b)
+      for (int j = 0; j < P; ++j) {
+        const int32_t tok = tokens[(size_t)b * P + j];
+        if (tok < 0 || tok >= c.vocab) return SKD_ERR_RANGE;
+        tr[(size_t)j * B + b] = tok;
+      }
+    HIPCHECK(hipMemcpyAsync(st->prompt_dev, tr.data(), tr.size() * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
+    HIPCHECK(hipStreamSynchronize(st->stream));
+    cols = st->prompt_dev;
+  }
+  HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  std::fill(st->kv_len.begin(), st->kv_len.end(), 0);
+  st->prefilled = false;
+  st->steps_done = 0;
+  for (int l = 0; l < c.L; ++l) st->layers_tmp[l] = l;  // the prompt uses every layer
+  for (int i = 0; i < P; ++i) SKDCHECK(run_column(st, i, cols + (size_t)i * B, st->layers_tmp.data(), c.L));
+  st->prefilled = true;
+  if (!c.io_on_device) HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
+}
+
+extern "C" int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_in) {
+  if (!st) return SKD_ERR_NULL;
+  const skd_config &c = st->cfg;
+  if (!st->prefilled) return SKD_ERR_ORDER;
+  if (t < 0 || t >= c.sequence_length) return SKD_ERR_RANGE;
+  if (t != c.prompt_size + st->steps_done) return SKD_ERR_ORDER;
+  const int32_t *tok = nullptr;
+  if (!tokens_in) {
+    if (!st->have_argmax) return SKD_ERR_ORDER;
+    tok = st->argmax_dev;
+  } else if (c.io_on_device) {
+    tok = tokens_in;
+  } else {
+    for (int b = 0; b < c.batch; ++b)
+      if (tokens_in[b] < 0 || tokens_in[b] >= c.vocab) return SKD_ERR_RANGE;
+    HIPCHECK(hipMemcpyAsync(st->tok_dev, tokens_in, c.batch * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
+    HIPCHECK(hipStreamSynchronize(st->stream));
+    tok = st->tok_dev;
+  }
+  const int n = skd_active_layers(t, &c, st->layers_tmp.data());
+  if (n < 0) return n;
+  SKDCHECK(run_column(st, t, tok, st->layers_tmp.data(), n));
+  st->steps_done += 1;
+  if (!c.io_on_device) HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
+}
+
+extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logits_out) {
+  if (!st) return SKD_ERR_NULL;
+  if (!st->have_hidden) return SKD_ERR_ORDER;
+  const skd_config &c = st->cfg;
+  const int B = c.batch, d = c.d_model, V = c.vocab;
+  hipStream_t s = st->stream;
+  float *logits_target = nullptr;  // where the kernels write logits, if anywhere
+  if (logits_out) logits_target = c.io_on_device ? logits_out : st->logits_dev;
+  if (!st->bf16) {
+    float *lg = logits_target ? logits_target : st->logits_dev;
+    f32_layernorm(s, st->x, st->lnf_g, st->lnf_b, (float *)st->a, B, d);
+    f32_linear(s, (const float *)st->head, nullptr, (const float *)st->a, lg, B, d, V, 0, 0);
+    f32_argmax(s, lg, st->argmax_dev, B, V);
+  } else {
+    GemmArgs ga{};
+    ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
+    ga.N = V; ga.K = d; ga.split = 1; ga.logits = logits_target; ga.pmax = st->pmax; ga.pidx = st->pidx;
+    const int groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R);
+    bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B);
+  }
+  HIPCHECK(hipGetLastError());
+  st->have_argmax = true;
+  if (c.io_on_device) {
+    if (tokens_out)
+      HIPCHECK(hipMemcpyAsync(tokens_out, st->argmax_dev, B * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    return SKD_OK;
+  }
+  if (tokens_out) HIPCHECK(hipMemcpyAsync(tokens_out, st->argmax_dev, B * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (logits_out)
+    HIPCHECK(hipMemcpyAsync(logits_out, st->logits_dev, (size_t)B * V * sizeof(float), hipMemcpyDeviceToHost, s));
+  HIPCHECK(hipStreamSynchronize(s));
+  return SKD_OK;
+}
+
+extern "C" int skd_kv_len(const skd_state *st, int32_t layer) {
+  if (!st) return SKD_ERR_NULL;
+  if (layer < 0 || layer >= st->cfg.L) return SKD_ERR_RANGE;
+  return st->kv_len[layer];
+}
+extern "C" int64_t skd_kv_pages_reserved(const skd_state *st) { return st ? st->pages_reserved : SKD_ERR_NULL; }
+extern "C" int64_t skd_kv_pages_dense(const skd_state *st) { return st ? st->pages_dense : SKD_ERR_NULL; }
+
+extern "C" int skd_synchronize(skd_state *st) {
+  if (!st) return SKD_ERR_NULL;
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
+}
+
+extern "C" int skd_debug_read_hidden(skd_state *st, float *x_out) {
+  if (!st || !x_out) return SKD_ERR_NULL;
+  if (!st->have_hidden) return SKD_ERR_ORDER;
+  HIPCHECK(hipMemcpyAsync(x_out, st->x, (size_t)st->cfg.batch * st->cfg.d_model * sizeof(float), hipMemcpyDeviceToHost,
+                          st->stream));
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
+}
+
+extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, const float *const *Vin) {
+  if (!st) return SKD_ERR_NULL;
+  const skd_config &c = st->cfg;
+  if (cols < c.prompt_size || cols >= c.sequence_length) return SKD_ERR_RANGE;
+  const int B = c.batch, d = c.d_model;
+  const size_t n = (size_t)B * cols * d;
+  float *kd = nullptr, *vd = nullptr;
+  HIPCHECK(hipMalloc((void **)&kd, n * sizeof(float)));
+  if (hipMalloc((void **)&vd, n * sizeof(float)) != hipSuccess) { (void)hipFree(kd); return SKD_ERR_NOMEM; }
+  int rc = SKD_OK;
+  for (int l = 0; l < c.L && rc == SKD_OK; ++l) {
+    if (st->kv_cap[l] < cols) {  // the layer left the window before column `cols`: it never runs again
+      st->kv_len[l] = st->kv_cap[l];
+      continue;
+    }
+    const float *ks = Kin ? Kin[l] : nullptr, *vs = Vin ? Vin[l] : nullptr;
+    const bool have = ks && vs;
+    if (have && (hipMemcpyAsync(kd, ks, n * sizeof(float), hipMemcpyHostToDevice, st->stream) != hipSuccess ||
+                 hipMemcpyAsync(vd, vs, n * sizeof(float), hipMemcpyHostToDevice, st->stream) != hipSuccess)) {
+      rc = SKD_ERR_HIP;
+      break;
+    }
+    if (st->bf16)
+      kv_load_bf16(st->stream, have ? kd : nullptr, have ? vd : nullptr, (bf16_t *)st->pool, bt_layer(st, l), cols, B, st->geom);
+    else
+      kv_load_f32(st->stream, have ? kd : nullptr, have ? vd : nullptr, (float *)st->pool, bt_layer(st, l), cols, B, st->geom);
+    if (hipStreamSynchronize(st->stream) != hipSuccess) { rc = SKD_ERR_HIP; break; }
+    st->kv_len[l] = cols;
+  }
+  (void)hipFree(kd);
+  (void)hipFree(vd);
+  if (rc != SKD_OK) return rc;
+  std::vector<int32_t> start(B, 0);
+  HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  st->prefilled = true;
+  st->steps_done = cols - c.prompt_size;
+  st->have_hidden = false;
+  st->have_argmax = false;
+  return SKD_OK;
+}
+
+extern "C" int skd_debug_kv_read(skd_state *st, int32_t layer, int32_t b, float *k_out, float *v_out) {
+  if (!st || !k_out || !v_out) return SKD_ERR_NULL;
+  const skd_config &c = st->cfg;
+  if (layer < 0 || layer >= c.L || b < 0 || b >= c.batch) return SKD_ERR_RANGE;
+  const int len = st->kv_len[layer], d = c.d_model;
+  if (len == 0) return SKD_OK;
+  float *kd = nullptr, *vd = nullptr;
+  HIPCHECK(hipMalloc((void **)&kd, (size_t)len * d * sizeof(float)));
+  if (hipMalloc((void **)&vd, (size_t)len * d * sizeof(float)) != hipSuccess) { (void)hipFree(kd); return SKD_ERR_NOMEM; }
+  const int32_t *row = bt_layer(st, layer) + (size_t)b * st->geom.max_pages;
+  if (st->bf16) kv_read_bf16(st->stream, (const bf16_t *)st->pool, row, len, kd, vd, st->geom);
+  else kv_read_f32(st->stream, (const float *)st->pool, row, len, kd, vd, st->geom);
+  int rc = SKD_OK;
+  if (hipMemcpyAsync(k_out, kd, (size_t)len * d * sizeof(float), hipMemcpyDeviceToHost, st->stream) != hipSuccess ||
+      hipMemcpyAsync(v_out, vd, (size_t)len * d * sizeof(float), hipMemcpyDeviceToHost, st->stream) != hipSuccess ||
+      hipStreamSynchronize(st->stream) != hipSuccess)
+    rc = SKD_ERR_HIP;
+  (void)hipFree(kd);
+  (void)hipFree(vd);
+  return rc;
+}

@@ -1,0 +1,106 @@
+// Internal launch interface between the host engine and the gfx950 kernels.
+// Not part of the public ABI (include/skd.h is).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace skd {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern in host-visible signatures
+
+// Geometry of the paged KV cache.  A page holds `page_tokens` consecutive
+// positions of ONE batch row in ONE layer, all heads.
+struct KvGeom {
+  int page_tokens;
+  int max_pages;      // block-table entries per (layer, row)
+  int H, dh;
+  long page_elems;    // elements (fp32 or bf16) per page = 2 * page_tokens * H * dh
+};
+
+// ---------------------------------------------------------------- fp32 debug path
+// Everything row-major fp32.  KV page layout: [K|V][page_tokens][H*dh].
+void f32_embed(hipStream_t s, float *x, const float *tok_emb, const float *pos_emb, const int32_t *tokens,
+               const int32_t *start, int t, int B, int d, int V);
+void f32_layernorm(hipStream_t s, const float *x, const float *g, const float *b, float *out, int B, int d);
+// out[b][n] = (accumulate ? out[b][n] : 0) + bias[n] + sum_k W[n][k] * in[b][k]; optional ReLU
+void f32_linear(hipStream_t s, const float *W, const float *bias, const float *in, float *out, int B, int K, int N,
+                int relu, int accumulate);
+void f32_kv_write(hipStream_t s, const float *qkv, float *pool, const int32_t *bt_layer, int t, int B, KvGeom g);
+void f32_attention(hipStream_t s, const float *qkv, const float *pool, const int32_t *bt_layer, const int32_t *start,
+                   int t, float *o, float *scores, int score_stride, int B, KvGeom g);
+void f32_argmax(hipStream_t s, const float *logits, int32_t *tokens, int B, int V);
+
+// ---------------------------------------------------------------- bf16 production path
+// "Fragment-major" layout of a [rows][K] bf16 matrix (weights: rows = output
+// features; activations: rows = batch rows padded to 16): 16-row x 32-column
+// fragments stored as 64 lanes x 8 elements, lane = (row % 16) + 16 * ((col % 32) / 8),
+// element = col % 8, fragments ordered [row / 16][col / 32].  One fragment is
+// exactly what one lane-wide 16-byte load feeds to v_mfma_f32_16x16x32_bf16.
+inline long frag_index(long row, long col, long K) {
+  return (((row / 16) * (K / 32) + col / 32) * 64 + (row % 16) + 16 * ((col % 32) / 8)) * 8 + col % 8;
+}
+
+enum GemmEpilogue {
+  EPI_PARTIAL = 0,  // fp32 partial sums [split][B_pad][N], no bias
+  EPI_QKV = 1,      // + bias; q -> row-major bf16, k/v -> KV page slot of position t
+  EPI_RELU = 2,     // + bias, ReLU -> fragment-major bf16 [B_pad][N]
+  EPI_LOGITS = 3    // optional fp32 logits [B][N] + per-workgroup (max, argmax) partials
+};
+
+struct GemmArgs {
+  const bf16_t *W;     // fragment-major [Nt_pad*16][K]
+  const bf16_t *A;     // fragment-major [B_pad][K]
+  const float *bias;   // [N] or null
+  int N, K, B, B_pad;
+  int split;           // workgroups along K (grid.y)
+  // outputs (by epilogue)
+  float *partial;      // EPI_PARTIAL
+  bf16_t *q_out;       // EPI_QKV: [B_pad][d] row-major
+  bf16_t *kv_pool;     // EPI_QKV
+  const int32_t *bt_layer;  // EPI_QKV: [B][max_pages]
+  int t;               // EPI_QKV: position being written
+  int d;               // EPI_QKV: d_model (N = 3d)
+  KvGeom kv;           // EPI_QKV
+  bf16_t *act_out;     // EPI_RELU
+  float *logits;       // EPI_LOGITS (nullable)
+  float *pmax;         // EPI_LOGITS: [groups][B_pad]
+  int32_t *pidx;       // EPI_LOGITS
+};
+// rows_per_wave_tiles R in {1,2,4}; returns number of row groups launched (grid.x)
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R);
+int bf16_gemm_groups(int N, int R);
+
+void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
+                   const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
+                   int V);
+// x[b][:] += bias + sum_s partial[s][b][:]; a_out = LayerNorm(x; g, b) fragment-major bf16
+void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
+                    const float *g, const float *b, bf16_t *a_out, int B, int d);
+struct AttnArgs {
+  const bf16_t *q;          // [B_pad][d] row-major
+  const bf16_t *pool;
+  const int32_t *bt_layer;  // [B][max_pages]
+  const int32_t *start;     // [B] first real column of each row
+  int t;                    // keys start[b] .. t
+  int B, splits;
+  KvGeom kv;
+  bf16_t *o;                // fragment-major [B_pad][d]
+  float *part;              // splits > 1: [splits][B*H][dh + 2]
+};
+void bf16_attention(hipStream_t s, const AttnArgs &a);
+void bf16_argmax_final(hipStream_t s, const float *pmax, const int32_t *pidx, int groups, int B_pad, int32_t *tokens,
+                       int B);
+
+// weight preparation (source fp32 or bf16 row-major, on device)
+void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long N, long K, long N_pad);
+void prep_matrix_rm_bf16(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long n);
+void prep_to_f32(hipStream_t s, const void *src, int src_is_bf16, float *dst, long n);
+// KV debug hooks: [B][cols][d] fp32 <-> pages
+void kv_load_f32(hipStream_t s, const float *K, const float *V, float *pool, const int32_t *bt_layer, int cols, int B,
+                 KvGeom g);
+void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer, int cols,
+                  int B, KvGeom g);
+void kv_read_f32(hipStream_t s, const float *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g);
+void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g);
+
+}  // namespace skd

@@ -1,0 +1,177 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the
+same seeded random-init weights and inputs, teacher-forced.
+
+Tolerances (max |delta logit| relative to the logit range of the step):
+  bf16 path  2e-2   -- weights/KV/activations rounded to bf16 (8 mantissa
+                       bits) between kernels, fp32 accumulation
+  fp32 path  1e-4   -- same arithmetic as the oracle up to summation order
+Schedule, layer indices and cache lengths must match exactly.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+from paper_2307_02628_amd import skd
+from tests.helpers import compare, rel_err, run_hip
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL, FP32_TOL = 2e-2, 1e-4
+
+
+def bf16_weights(shape, seed):
+    return S.weights_to_bf16_values(S.make_weights(shape, seed))
+
+
+def test_config1_fp32():
+    # contract configuration 1 on the fp32 debug build of the path
+    w = S.make_weights(S.TINY, 0)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    got, ref, err = compare(S.TINY, w, pr, 16, 32, 2, 4, FP32_TOL, dtype=skd.FP32)
+    assert [len(a) for a in got["layers"]] == [4] * 5 + [3] * 8 + [2] * 3
+    print("fp32 config-1 per-step error:", err.max())
+
+
+def test_config1_bf16():
+    w = bf16_weights(S.TINY, 0)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    got, ref, err = compare(S.TINY, w, pr, 16, 32, 2, 4, BF16_TOL, dtype=skd.BF16)
+    assert got["pages"][0] < got["pages"][1] or got["pages"][0] == got["pages"][1]
+    print("bf16 config-1 per-step error:", err.max())
+
+
+def test_config1_full_depth_both():
+    # n(t) = L everywhere: ordinary decoding
+    for dtype, tol, w in ((skd.FP32, FP32_TOL, S.make_weights(S.TINY, 0)), (skd.BF16, BF16_TOL, bf16_weights(S.TINY, 0))):
+        pr = S.make_prompts(2, 16, S.TINY.V, 1)
+        compare(S.TINY, w, pr, 16, 32, 4, 4, tol, dtype=dtype)
+
+
+MID = S.ModelShape(L=3, d=512, H=4, f=1536, V=1000, max_pos=128)      # head_dim 128, vocab tail (1000 % 16 != 0)
+MID64 = S.ModelShape(L=5, d=384, H=6, f=1024, V=777, max_pos=160)     # head_dim 64
+
+
+@pytest.mark.parametrize("dtype,tol", [(skd.FP32, FP32_TOL), (skd.BF16, BF16_TOL)])
+def test_mid_ragged_left_padded(dtype, tol):
+    # several KV pages and 32-key blocks, ragged batch (5 rows), left padding, page size 32
+    w = S.make_weights(MID, 2)
+    if dtype == skd.BF16:
+        w = S.weights_to_bf16_values(w)
+    B, P, N = 5, 40, 90
+    pr = S.make_prompts(B, P, MID.V, 3)
+    mask = S.make_ragged_mask(B, P, 1, 40, seed=4)
+    mask[0] = 1
+    mask[1] = 0
+    mask[1, -1] = 1                                                    # a row with a single real prompt token
+    compare(MID, w, pr, P, N, 1, 3, tol, mask=mask, dtype=dtype, page_tokens=32)
+
+
+@pytest.mark.parametrize("B", [1, 16, 17, 33])
+def test_batch_tiles_bf16(B):
+    w = bf16_weights(MID64, 5)
+    P, N = 9, 30
+    pr = S.make_prompts(B, P, MID64.V, 6)
+    compare(MID64, w, pr, P, N, 2, 5, BF16_TOL, dtype=skd.BF16)
+
+
+@pytest.mark.parametrize("dtype,tol", [(skd.FP32, FP32_TOL), (skd.BF16, BF16_TOL)])
+def test_warmup_layer(dtype, tol):
+    # one warm-up layer at the bottom + top window (the setting of every Table 2 row)
+    w = S.make_weights(MID64, 7)
+    if dtype == skd.BF16:
+        w = S.weights_to_bf16_values(w)
+    pr = S.make_prompts(3, 12, MID64.V, 8)
+    got, ref, _ = compare(MID64, w, pr, 12, 40, 2, 4, tol, warmup=1, dtype=dtype)
+    assert all(a[0] == 0 and a[1] >= 2 for a in got["layers"][4:])
+
+
+def test_free_running_equals_teacher_forced():
+    w = bf16_weights(S.TINY, 0)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    free = run_hip(S.TINY, w, pr, 16, 32, 2, 4, dtype=skd.BF16)
+    forced = run_hip(S.TINY, w, pr, 16, 32, 2, 4, tape=free["fed"], dtype=skd.BF16)
+    np.testing.assert_array_equal(free["logits"], forced["logits"])    # deterministic kernels
+    for k in range(16):
+        np.testing.assert_array_equal(free["fed"][k], free["logits"][k].argmax(-1))
+
+
+def test_kv_bookkeeping_and_pages():
+    w = bf16_weights(S.TINY, 0)
+    cfg = skd.make_config(S.TINY, 2, 16, 32, 2, 4, page_tokens=32)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    with skd.Decoder(cfg, w) as dec:
+        res, dense = dec.kv_pages()
+        assert dense == 4 * 2 * 1 and res == dense          # 32 tokens = one page per (layer,row) either way
+        dec.prefill(pr)
+        assert [dec.kv_len(l) for l in range(4)] == [16] * 4
+        total = 16 * 4
+        for k in range(16):
+            t = 16 + k
+            act = skd.skd_active_layers(t, cfg)
+            for l in act:
+                assert dec.kv_len(l) == t                    # every earlier key exists: nothing to recompute
+            dec.decode_step(t, pr[:, k])
+            total += len(act)
+            assert sum(dec.kv_len(l) for l in range(4)) == total
+    cfg2 = skd.make_config(S.TINY, 2, 32, 64, 1, 2, page_tokens=32)   # bottom layers stop after the prompt
+    with skd.Decoder(cfg2, w) as dec:
+        res, dense = dec.kv_pages()
+        assert dense == 4 * 2 * 2 and res == 2 * (1 + 1 + 2 + 2)
+
+
+def test_call_order_and_range_errors():
+    w = bf16_weights(S.TINY, 0)
+    cfg = skd.make_config(S.TINY, 2, 16, 32, 2, 4)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    tok = np.array([1, 2], np.int32)
+    with skd.Decoder(cfg, w) as dec:
+        assert dec.decode_step_rc(16, tok) == skd.ERR_ORDER          # no prefill yet
+        assert dec._lib.skd_logits_argmax(dec._h, None, None) == skd.ERR_ORDER
+        bad = pr.copy()
+        bad[0, 3] = S.TINY.V
+        assert dec.prefill_rc(bad) == skd.ERR_RANGE
+        m = np.ones((2, 16), np.uint8)
+        m[0, 5] = 0                                                   # hole: not left padding
+        assert dec.prefill_rc(pr, m) == skd.ERR_SHAPE
+        m = np.ones((2, 16), np.uint8)
+        m[1] = 0                                                      # empty row
+        assert dec.prefill_rc(pr, m) == skd.ERR_SHAPE
+        dec.prefill(pr)
+        assert dec.decode_step_rc(17, tok) == skd.ERR_ORDER          # wrong position
+        assert dec.decode_step_rc(16, None) == skd.ERR_ORDER         # no argmax to continue from
+        assert dec.decode_step_rc(16, np.array([1, -1], np.int32)) == skd.ERR_RANGE
+        assert dec.decode_step_rc(32, tok) == skd.ERR_RANGE          # t >= N
+        dec.decode_step(16, tok)
+        assert dec.decode_step_rc(16, tok) == skd.ERR_ORDER          # same column twice
+        dec.logits_argmax()
+        dec.decode_step(17, None)
+        # a second prefill restarts the generation
+        dec.prefill(pr)
+        assert [dec.kv_len(l) for l in range(4)] == [16] * 4
+        dec.decode_step(16, tok)
+
+
+def test_device_io_mode_matches_host_io():
+    import torch
+    w = bf16_weights(S.TINY, 0)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    tape = S.make_token_tape(2, 16, S.TINY.V, 9)
+    host = run_hip(S.TINY, w, pr, 16, 32, 2, 4, tape=tape, dtype=skd.BF16)
+    cfg = skd.make_config(S.TINY, 2, 16, 32, 2, 4, io_on_device=1)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        pr_dev = torch.from_numpy(np.ascontiguousarray(pr.T)).cuda()           # [P][B]
+        tape_dev = torch.from_numpy(tape).cuda()
+        logits = torch.zeros(17, 2, S.TINY.V, dtype=torch.float32, device="cuda")
+        toks = torch.zeros(17, 2, dtype=torch.int32, device="cuda")
+        stream.synchronize()
+        with skd.Decoder(cfg, w, stream=stream.cuda_stream) as dec:
+            dec.prefill(pr_dev)
+            dec.logits_argmax_device(toks[0], logits[0])
+            for k in range(16):
+                dec.decode_step(16 + k, tape_dev[k])
+                dec.logits_argmax_device(toks[k + 1], logits[k + 1])
+            dec.synchronize()
+        np.testing.assert_array_equal(logits.cpu().numpy(), host["logits"])
+        np.testing.assert_array_equal(toks.cpu().numpy(), host["logits"].argmax(-1))
