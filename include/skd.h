@@ -158,6 +158,15 @@ int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_in);
  * processed yet), SKD_ERR_HIP. */
 int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logits_out);
 
+/* Move the generation back to position t (P <= t <= current position): the
+ * next skd_decode_step must be for column t; cache entries at columns >= t are
+ * forgotten (they are overwritten when those columns are processed again).
+ * The static schedule makes this exact: which layers hold which columns only
+ * depends on t.  Used to regenerate from a point and to time a run after a
+ * warm-up without repeating the prompt.  Errors: SKD_ERR_NULL, SKD_ERR_ORDER
+ * (no prefill), SKD_ERR_RANGE. */
+int skd_rewind(skd_state *st, int32_t t);
+
 /* Number of columns layer `layer`'s KV cache holds (host bookkeeping).  For a
  * layer active at t this equals t before the step and t + 1 after it. */
 int skd_kv_len(const skd_state *st, int32_t layer);
@@ -188,6 +197,29 @@ int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, cons
 /* Read back row b of layer l's cache: k_out, v_out [len][d] fp32 with
  * len = skd_kv_len(l). */
 int skd_debug_kv_read(skd_state *st, int32_t layer, int32_t b, float *k_out, float *v_out);
+
+/* Per-kernel timing.  While enabled, every kernel launch of this state is
+ * bracketed by two HIP events on the state's stream (this serialises nothing
+ * but costs a little per launch, so time whole runs with it off).
+ * skd_profile_read waits for the stream and adds the elapsed milliseconds and
+ * launch counts per kernel class into ms[SKD_PROF_CLASSES] and
+ * launches[SKD_PROF_CLASSES] (either may be NULL), then clears the internal
+ * accumulators.  Classes: see skd_prof_class. */
+typedef enum {
+  SKD_PROF_EMBED_LN = 0, /* embedding gather + first LayerNorm */
+  SKD_PROF_GEMM_QKV = 1, /* q,k,v projection + KV page write  */
+  SKD_PROF_ATTENTION = 2,/* decode attention over the paged KV (incl. split merge) */
+  SKD_PROF_GEMM_OUT = 3, /* attention output projection        */
+  SKD_PROF_REDUCE_LN = 4,/* split-K reduce + bias + residual + LayerNorm */
+  SKD_PROF_GEMM_FFN1 = 5,
+  SKD_PROF_GEMM_FFN2 = 6,
+  SKD_PROF_LM_HEAD = 7,  /* LM head projection with per-workgroup argmax */
+  SKD_PROF_ARGMAX = 8,   /* final argmax reduction             */
+  SKD_PROF_OTHER = 9,    /* fp32 debug path kernels            */
+  SKD_PROF_CLASSES = 10
+} skd_prof_class;
+int skd_profile_enable(skd_state *st, int32_t on);
+int skd_profile_read(skd_state *st, double *ms, int64_t *launches);
 
 void skd_destroy(skd_state *st);
 const char *skd_strerror(int err);

@@ -96,6 +96,11 @@ def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data
 
 
+def threads(real: str = "f64") -> int:
+    """OpenMP threads the oracle's parallel loops use."""
+    return int(_lib(real).ora_threads())
+
+
 def schedule(i: int, P: int, N: int, n_min: int, n_max: int, L: int, real: str = "f64") -> int:
     """n(i); raises OracleError on invalid parameters."""
     return _check(_lib(real).ora_schedule(i, P, N, n_min, n_max, L), "schedule")

@@ -80,6 +80,13 @@ typedef struct {
 
 int ora_real_bytes(void) { return (int)sizeof(real); }
 
+#ifdef _OPENMP
+#include <omp.h>
+int ora_threads(void) { return omp_get_max_threads(); }
+#else
+int ora_threads(void) { return 1; }
+#endif
+
 /* ------------------------------------------------------------------ */
 /* Schedule (Section 2.3)                                              */
 /* ------------------------------------------------------------------ */

@@ -87,6 +87,13 @@ struct skd_state {
   bool prefilled = false, have_hidden = false, have_argmax = false;
   int steps_done = 0;
   std::vector<int32_t> layers_tmp;
+  // per-kernel timing (off by default)
+  bool profiling = false;
+  struct ProfRec { int cls; hipEvent_t a, b; };
+  std::vector<ProfRec> prof_pending;
+  std::vector<hipEvent_t> prof_free;
+  double prof_ms[SKD_PROF_CLASSES] = {};
+  int64_t prof_n[SKD_PROF_CLASSES] = {};
 };
 
 namespace {
@@ -242,6 +249,50 @@ int build_kv(skd_state *st) {
   return SKD_OK;
 }
 
+hipEvent_t prof_event(skd_state *st) {
+  if (!st->prof_free.empty()) {
+    hipEvent_t e = st->prof_free.back();
+    st->prof_free.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+// brackets the launches issued inside its scope with two events when profiling is on
+struct ProfScope {
+  skd_state *st;
+  int cls;
+  hipEvent_t a = nullptr;
+  ProfScope(skd_state *s, int c) : st(s), cls(c) {
+    if (st->profiling) {
+      a = prof_event(st);
+      if (a) (void)hipEventRecord(a, st->stream);
+    }
+  }
+  ~ProfScope() {
+    if (a) {
+      hipEvent_t b = prof_event(st);
+      if (b) (void)hipEventRecord(b, st->stream);
+      st->prof_pending.push_back({cls, a, b});
+    }
+  }
+};
+int prof_drain(skd_state *st) {
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  for (auto &r : st->prof_pending) {
+    float ms = 0.f;
+    if (r.a && r.b && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+      st->prof_ms[r.cls] += ms;
+      st->prof_n[r.cls] += 1;
+    }
+    if (r.a) st->prof_free.push_back(r.a);
+    if (r.b) st->prof_free.push_back(r.b);
+  }
+  st->prof_pending.clear();
+  return SKD_OK;
+}
+
 const int32_t *bt_layer(const skd_state *st, int l) {
   return st->bt_dev + (size_t)l * st->cfg.batch * st->geom.max_pages;
 }
@@ -259,26 +310,23 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
   }
   if (!st->bf16) {
     float *a = (float *)st->a, *qkv = (float *)st->q, *o = (float *)st->o, *u = (float *)st->u;
-    f32_embed(s, st->x, (const float *)st->tok_emb, (const float *)st->pos_emb, tokens_dev, st->start_dev, t, B, d,
-              c.vocab);
+    { ProfScope ps_(st, SKD_PROF_OTHER); f32_embed(s, st->x, (const float *)st->tok_emb, (const float *)st->pos_emb, tokens_dev, st->start_dev, t, B, d, c.vocab); }
     for (int i = 0; i < n; ++i) {
       const LayerW &w = st->lw[layers[i]];
-      f32_layernorm(s, st->x, w.ln1_g, w.ln1_b, a, B, d);
-      f32_linear(s, (const float *)w.wqkv, w.bqkv, a, qkv, B, d, 3 * d, 0, 0);
-      f32_kv_write(s, qkv, (float *)st->pool, bt_layer(st, layers[i]), t, B, st->geom);
-      f32_attention(s, qkv, (const float *)st->pool, bt_layer(st, layers[i]), st->start_dev, t, o, st->attn_part,
-                    c.sequence_length, B, st->geom);
-      f32_linear(s, (const float *)w.wo, w.bo, o, st->x, B, d, d, 0, 1);
-      f32_layernorm(s, st->x, w.ln2_g, w.ln2_b, a, B, d);
-      f32_linear(s, (const float *)w.w1, w.b1, a, u, B, d, f, 1, 0);
-      f32_linear(s, (const float *)w.w2, w.b2, u, st->x, B, f, d, 0, 1);
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_layernorm(s, st->x, w.ln1_g, w.ln1_b, a, B, d); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_linear(s, (const float *)w.wqkv, w.bqkv, a, qkv, B, d, 3 * d, 0, 0); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_kv_write(s, qkv, (float *)st->pool, bt_layer(st, layers[i]), t, B, st->geom); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_attention(s, qkv, (const float *)st->pool, bt_layer(st, layers[i]), st->start_dev, t, o, st->attn_part, c.sequence_length, B, st->geom); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_linear(s, (const float *)w.wo, w.bo, o, st->x, B, d, d, 0, 1); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_layernorm(s, st->x, w.ln2_g, w.ln2_b, a, B, d); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_linear(s, (const float *)w.w1, w.b1, a, u, B, d, f, 1, 0); }
+      { ProfScope ps_(st, SKD_PROF_OTHER); f32_linear(s, (const float *)w.w2, w.b2, u, st->x, B, f, d, 0, 1); }
       st->kv_len[layers[i]] = t + 1;
     }
   } else {
     bf16_t *a = (bf16_t *)st->a, *q = (bf16_t *)st->q, *o = (bf16_t *)st->o, *u = (bf16_t *)st->u;
     const LayerW &w0 = st->lw[layers[0]];
-    bf16_embed_ln(s, tokens_dev, st->start_dev, t, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, w0.ln1_g,
-                  w0.ln1_b, st->x, a, B, d, c.vocab);
+    { ProfScope ps_(st, SKD_PROF_EMBED_LN); bf16_embed_ln(s, tokens_dev, st->start_dev, t, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, w0.ln1_g, w0.ln1_b, st->x, a, B, d, c.vocab); }
     for (int i = 0; i < n; ++i) {
       const int l = layers[i];
       const LayerW &w = st->lw[l];
@@ -287,24 +335,24 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       // q, k, v projection; k and v go straight into this layer's page slot for column t
       ga.W = (const bf16_t *)w.wqkv; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
       ga.q_out = q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
-      bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R);
+      { ProfScope ps_(st, SKD_PROF_GEMM_QKV); bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R); }
       AttnArgs aa{};
       aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
       aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
-      bf16_attention(s, aa);
+      { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
       ga.W = (const bf16_t *)w.wo; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
-      bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R);
-      bf16_reduce_ln(s, st->partial, st->p_out.split, st->B_pad, w.bo, st->x, w.ln2_g, w.ln2_b, a, B, d);
+      { ProfScope ps_(st, SKD_PROF_GEMM_OUT); bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R); }
+      { ProfScope ps_(st, SKD_PROF_REDUCE_LN); bf16_reduce_ln(s, st->partial, st->p_out.split, st->B_pad, w.bo, st->x, w.ln2_g, w.ln2_b, a, B, d); }
       ga.W = (const bf16_t *)w.w1; ga.A = a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.split = 1; ga.act_out = u;
-      bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R);
+      { ProfScope ps_(st, SKD_PROF_GEMM_FFN1); bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R); }
       ga.W = (const bf16_t *)w.w2; ga.A = u; ga.N = d; ga.K = f; ga.split = st->p_ffn2.split;
-      bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R);
+      { ProfScope ps_(st, SKD_PROF_GEMM_FFN2); bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R); }
       // the reducer of the last sub-block already applies the next LayerNorm:
       // LayerNorm 1 of the next ACTIVE layer, or the final LayerNorm
       const float *ng = (i + 1 < n) ? st->lw[layers[i + 1]].ln1_g : st->lnf_g;
       const float *nb = (i + 1 < n) ? st->lw[layers[i + 1]].ln1_b : st->lnf_b;
-      bf16_reduce_ln(s, st->partial, st->p_ffn2.split, st->B_pad, w.b2, st->x, ng, nb, a, B, d);
+      { ProfScope ps_(st, SKD_PROF_REDUCE_LN); bf16_reduce_ln(s, st->partial, st->p_ffn2.split, st->B_pad, w.b2, st->x, ng, nb, a, B, d); }
       st->kv_len[l] = t + 1;
     }
   }
@@ -429,6 +477,8 @@ extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip
 extern "C" void skd_destroy(skd_state *st) {
   if (!st) return;
   (void)hipStreamSynchronize(st->stream);
+  for (auto &r : st->prof_pending) { if (r.a) (void)hipEventDestroy(r.a); if (r.b) (void)hipEventDestroy(r.b); }
+  for (hipEvent_t e : st->prof_free) (void)hipEventDestroy(e);
   for (void *p : st->allocs) (void)hipFree(p);
   delete st;
 }
@@ -512,15 +562,16 @@ extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logi
   if (logits_out) logits_target = c.io_on_device ? logits_out : st->logits_dev;
   if (!st->bf16) {
     float *lg = logits_target ? logits_target : st->logits_dev;
-    f32_layernorm(s, st->x, st->lnf_g, st->lnf_b, (float *)st->a, B, d);
-    f32_linear(s, (const float *)st->head, nullptr, (const float *)st->a, lg, B, d, V, 0, 0);
-    f32_argmax(s, lg, st->argmax_dev, B, V);
+    { ProfScope ps_(st, SKD_PROF_OTHER); f32_layernorm(s, st->x, st->lnf_g, st->lnf_b, (float *)st->a, B, d); }
+    { ProfScope ps_(st, SKD_PROF_OTHER); f32_linear(s, (const float *)st->head, nullptr, (const float *)st->a, lg, B, d, V, 0, 0); }
+    { ProfScope ps_(st, SKD_PROF_OTHER); f32_argmax(s, lg, st->argmax_dev, B, V); }
   } else {
     GemmArgs ga{};
     ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
     ga.N = V; ga.K = d; ga.split = 1; ga.logits = logits_target; ga.pmax = st->pmax; ga.pidx = st->pidx;
-    const int groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R);
-    bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B);
+    int groups = 0;
+    { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R); }
+    { ProfScope ps_(st, SKD_PROF_ARGMAX); bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B); }
   }
   HIPCHECK(hipGetLastError());
   st->have_argmax = true;
@@ -533,6 +584,37 @@ extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logi
   if (logits_out)
     HIPCHECK(hipMemcpyAsync(logits_out, st->logits_dev, (size_t)B * V * sizeof(float), hipMemcpyDeviceToHost, s));
   HIPCHECK(hipStreamSynchronize(s));
+  return SKD_OK;
+}
+
+extern "C" int skd_rewind(skd_state *st, int32_t t) {
+  if (!st) return SKD_ERR_NULL;
+  if (!st->prefilled) return SKD_ERR_ORDER;
+  const skd_config &c = st->cfg;
+  if (t < c.prompt_size || t > c.prompt_size + st->steps_done) return SKD_ERR_RANGE;
+  for (int l = 0; l < c.L; ++l) st->kv_len[l] = std::min(st->kv_len[l], (int)t);
+  st->steps_done = t - c.prompt_size;
+  st->have_hidden = false;  // the residual stream on the device belongs to a later column
+  st->have_argmax = false;
+  return SKD_OK;
+}
+
+extern "C" int skd_profile_enable(skd_state *st, int32_t on) {
+  if (!st) return SKD_ERR_NULL;
+  SKDCHECK(prof_drain(st));
+  st->profiling = on != 0;
+  return SKD_OK;
+}
+
+extern "C" int skd_profile_read(skd_state *st, double *ms, int64_t *launches) {
+  if (!st) return SKD_ERR_NULL;
+  SKDCHECK(prof_drain(st));
+  for (int i = 0; i < SKD_PROF_CLASSES; ++i) {
+    if (ms) ms[i] = st->prof_ms[i];
+    if (launches) launches[i] = st->prof_n[i];
+    st->prof_ms[i] = 0;
+    st->prof_n[i] = 0;
+  }
   return SKD_OK;
 }
 

@@ -22,7 +22,7 @@ HOST, DEVICE = 0, 1
 W_FP32, W_BF16 = 0, 1
 
 EXPORTS = ["skd_schedule", "skd_active_layers", "skd_create", "skd_prefill", "skd_decode_step",
-           "skd_logits_argmax", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
+           "skd_logits_argmax", "skd_rewind", "skd_profile_enable", "skd_profile_read", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
            "skd_debug_read_hidden", "skd_debug_kv_load", "skd_debug_kv_read", "skd_destroy", "skd_strerror",
            "skd_last_hip_error"]
 
@@ -44,6 +44,8 @@ class Weights(C.Structure):
                                     "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")])
 
 
+PROF_CLASSES = ("embed_ln", "gemm_qkv", "attention", "gemm_out", "reduce_ln", "gemm_ffn1", "gemm_ffn2", "lm_head",
+                "argmax", "other")
 PER_LAYER = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
 
 _lib: Optional[C.CDLL] = None
@@ -63,6 +65,9 @@ def lib() -> C.CDLL:
         l.skd_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         l.skd_logits_argmax.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        l.skd_rewind.argtypes = [C.c_void_p, C.c_int32]
+        l.skd_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+        l.skd_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_kv_len.argtypes = [C.c_void_p, C.c_int32]
         l.skd_kv_pages_reserved.argtypes = [C.c_void_p]
         l.skd_kv_pages_reserved.restype = C.c_int64
@@ -206,6 +211,18 @@ class Decoder:
     def logits_argmax_device(self, tokens_out=None, logits_out=None):
         """Device-I/O form: pointers / torch tensors on the device; asynchronous."""
         _check(self._lib.skd_logits_argmax(self._h, _ptr_of(tokens_out), _ptr_of(logits_out)), "skd_logits_argmax")
+
+    def rewind(self, t: int):
+        _check(self._lib.skd_rewind(self._h, t), "skd_rewind")
+
+    def profile_enable(self, on: bool):
+        _check(self._lib.skd_profile_enable(self._h, int(on)), "skd_profile_enable")
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        ms = (C.c_double * len(PROF_CLASSES))()
+        n = (C.c_int64 * len(PROF_CLASSES))()
+        _check(self._lib.skd_profile_read(self._h, ms, n), "skd_profile_read")
+        return {name: {"ms": float(ms[i]), "launches": int(n[i])} for i, name in enumerate(PROF_CLASSES)}
 
     # -- bookkeeping and hooks
     def kv_len(self, layer: int) -> int:
