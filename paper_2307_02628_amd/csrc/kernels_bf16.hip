@@ -113,10 +113,9 @@ __device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0,
   *(uint2 *)&a.act_out[d_frag_index(b, n0, a.N)] = pk;
 }
 
-template <int MB, int R, int EPI>
+template <int MB, int R, int EPI, int U>
 __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
-  constexpr int U = (R * MB >= 8) ? 1 : 2;  // k-steps per register buffer
-  constexpr int RM = R * MB;
+  constexpr int RM = R * MB;  // U = k-steps per register buffer
   extern __shared__ floatx4 red[];  // [4 waves][RM][64 lanes]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int Kf = a.K >> 5;
@@ -234,36 +233,48 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
 
 int bf16_gemm_groups(int N, int R) { return (N + 16 * R - 1) / (16 * R); }
 
-template <int MB, int R>
+template <int MB, int R, int U>
 static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid, size_t lds) {
   switch (epi) {
-    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL>), grid, dim3(256), lds, s, a); break;
-    case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV>), grid, dim3(256), lds, s, a); break;
-    case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU>), grid, dim3(256), lds, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS>), grid, dim3(256), lds, s, a); break;
+    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL, U>), grid, dim3(256), lds, s, a); break;
+    case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV, U>), grid, dim3(256), lds, s, a); break;
+    case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU, U>), grid, dim3(256), lds, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U>), grid, dim3(256), lds, s, a); break;
   }
 }
+template <int MB, int R>
+static void launch_gemm_u(hipStream_t s, const GemmArgs &a, int epi, int U, dim3 grid, size_t lds) {
+  // register budget: two buffers of U * (R + MB) fragments plus R * MB accumulators
+  if constexpr ((R + MB) * 4 <= 24) {
+    if (U >= 4) { launch_gemm_epi<MB, R, 4>(s, a, epi, grid, lds); return; }
+  }
+  if constexpr ((R + MB) * 2 <= 24) {
+    if (U >= 2) { launch_gemm_epi<MB, R, 2>(s, a, epi, grid, lds); return; }
+  }
+  launch_gemm_epi<MB, R, 1>(s, a, epi, grid, lds);
+}
 template <int MB>
-static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, dim3 grid) {
+static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int U, dim3 grid) {
   const size_t lds = (size_t)4 * R * MB * 64 * sizeof(floatx4);
-  if (R == 1) launch_gemm_epi<MB, 1>(s, a, epi, grid, lds);
-  else if (R == 2) launch_gemm_epi<MB, 2>(s, a, epi, grid, lds);
-  else launch_gemm_epi<MB, 4>(s, a, epi, grid, lds);
+  if (R == 1) launch_gemm_u<MB, 1>(s, a, epi, U, grid, lds);
+  else if (R == 2) launch_gemm_u<MB, 2>(s, a, epi, U, grid, lds);
+  else launch_gemm_u<MB, 4>(s, a, epi, U, grid, lds);
 }
 
 // Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}; the
 // cross-wave reduction buffer (4 * R * MB KiB of LDS) caps R for wide batches.
-int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R) {
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U) {
   const int MB = a.B_pad / 16;
   if (MB >= 8) R = 1;
   else if (MB >= 4 && R > 2) R = 2;
+  if (R == 3) R = 2;
   const int groups = bf16_gemm_groups(a.N, R);
   const dim3 grid(groups, epi == EPI_LOGITS ? 1 : a.split);
   switch (MB) {
-    case 1: launch_gemm_r<1>(s, a, epi, R, grid); break;
-    case 2: launch_gemm_r<2>(s, a, epi, R, grid); break;
-    case 4: launch_gemm_r<4>(s, a, epi, R, grid); break;
-    case 8: launch_gemm_r<8>(s, a, epi, R, grid); break;
+    case 1: launch_gemm_r<1>(s, a, epi, R, U, grid); break;
+    case 2: launch_gemm_r<2>(s, a, epi, R, U, grid); break;
+    case 4: launch_gemm_r<4>(s, a, epi, R, U, grid); break;
+    case 8: launch_gemm_r<8>(s, a, epi, R, U, grid); break;
     default: return -1;
   }
   return groups;
@@ -309,25 +320,36 @@ void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, i
 }
 
 // ------------------------------------------------------------------ split-K reduce + bias + residual + LayerNorm
-__global__ __launch_bounds__(256) void k_reduce_ln(const float *partial, int split, int B_pad, const float *bias,
-                                                   float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
+// One 1024-thread workgroup per batch row; each thread owns float4 chunks of
+// the row and issues all of its partial-sum loads before using any of them
+// (the kernel is a dependent-latency chain otherwise: it moves < 1 MB).
+__global__ __launch_bounds__(1024) void k_reduce_ln(const float *partial, int split, int B_pad, const float *bias,
+                                                    float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
   extern __shared__ float row[];
-  __shared__ float sh[4];
-  const int b = blockIdx.x;
+  __shared__ float sh[16];
+  const int b = blockIdx.x, d4 = d >> 2;
+  const floatx4 *p4 = (const floatx4 *)partial;
+  floatx4 *x4 = (floatx4 *)x + (long)b * d4;
+  const floatx4 *bias4 = (const floatx4 *)bias;
   float s = 0;
-  for (int k = threadIdx.x; k < d; k += 256) {
-    float v = partial[(long)b * d + k];
-    for (int sp = 1; sp < split; ++sp) v += partial[((long)sp * B_pad + b) * d + k];  // fixed order
-    v = x[(long)b * d + k] + (v + bias[k]);
-    row[k] = v;
-    x[(long)b * d + k] = v;
-    s += v;
+  for (int c = threadIdx.x; c < d4; c += 1024) {
+    floatx4 xv = x4[c], bv = bias4[c];
+    floatx4 v = p4[(long)b * d4 + c];
+#pragma unroll 8
+    for (int sp = 1; sp < split; ++sp) v += p4[((long)sp * B_pad + b) * d4 + c];  // fixed order
+    v = xv + (v + bv);
+    x4[c] = v;
+    *(floatx4 *)&row[4 * c] = v;
+    s += (v[0] + v[1]) + (v[2] + v[3]);
   }
   const float mean = block_sum_f(s, sh) / d;
   float q = 0;
-  for (int k = threadIdx.x; k < d; k += 256) q += (row[k] - mean) * (row[k] - mean);
+  for (int c = threadIdx.x; c < d4; c += 1024) {
+    const floatx4 v = *(floatx4 *)&row[4 * c] - mean;
+    q += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+  }
   const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
-  for (int k8 = threadIdx.x; k8 < d / 8; k8 += 256) {
+  for (int k8 = threadIdx.x; k8 < d / 8; k8 += 1024) {
     uint32_t pk[4];
     for (int j = 0; j < 4; ++j) {
       const int k = k8 * 8 + 2 * j;
@@ -339,7 +361,7 @@ __global__ __launch_bounds__(256) void k_reduce_ln(const float *partial, int spl
 
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d) {
-  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(256), d * sizeof(float), s, partial, split, B_pad, bias, x, g, b,
+  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(1024), d * sizeof(float), s, partial, split, B_pad, bias, x, g, b,
                      a_out, d);
 }
 

@@ -66,8 +66,9 @@ struct GemmArgs {
   float *pmax;         // EPI_LOGITS: [groups][B_pad]
   int32_t *pidx;       // EPI_LOGITS
 };
-// rows_per_wave_tiles R in {1,2,4}; returns number of row groups launched (grid.x)
-int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R);
+// R in {1,2,4}: 16-row weight tiles per wave; U in {1,2,4}: k-steps per register buffer (prefetch depth).
+// Returns the number of row groups launched (grid.x).
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U);
 int bf16_gemm_groups(int N, int R);
 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
