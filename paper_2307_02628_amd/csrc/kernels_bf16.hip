@@ -67,11 +67,10 @@ __device__ inline long kv_v_off(int h, int tt, int e, const KvGeom &g) {
 
 // ------------------------------------------------------------------ skinny GEMM
 // C[b][n] = sum_k A[b][k] * W[n][k], batch on the MFMA column side.
-// Workgroup = 4 waves that split the workgroup's K range and share the same
-// 16*R weight rows; grid.y splits K further across workgroups.  Each wave
-// streams R weight-fragment rows and MB activation fragments per 32-wide
-// k-step with two register buffers of U k-steps (loads for the next buffer are
-// in flight while the MFMAs of the current one issue).
+// Workgroup = 4 or 8 waves that share the same 16*R weight rows and interleave
+// the workgroup's K range among themselves; grid.y splits K further across
+// workgroups.  Each wave streams R weight-fragment rows and MB activation
+// fragments per 32-wide k-step through two register buffers of U k-steps.
 template <int EPI>
 __device__ inline void gemm_epilogue(const GemmArgs &a, int b, int n0, floatx4 v, int grp);
 
@@ -113,16 +112,19 @@ __device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0,
   *(uint2 *)&a.act_out[d_frag_index(b, n0, a.N)] = pk;
 }
 
-template <int MB, int R, int EPI, int U>
-__global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
-  constexpr int RM = R * MB;  // U = k-steps per register buffer
-  extern __shared__ floatx4 red[];  // [4 waves][RM][64 lanes]
+template <int MB, int R, int EPI, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
+  constexpr int RM = R * MB;
+  extern __shared__ floatx4 red[];  // [WAVES][RM][64 lanes]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int Kf = a.K >> 5;
-  const int slots = a.split * 4, slot = blockIdx.y * 4 + wave;
-  const int kf0 = (int)((long)Kf * slot / slots), kf1 = (int)((long)Kf * (slot + 1) / slots);
-  const bf16x8 *Wb = (const bf16x8 *)a.W + ((long)blockIdx.x * R * Kf) * 64 + lane;
-  const bf16x8 *Ab = (const bf16x8 *)a.A + lane;
+  // K range of this workgroup, cut into buffers of U k-steps that are dealt
+  // round-robin to the waves: at any moment the workgroup reads WAVES * U KiB
+  // of consecutive addresses from each of its R weight-row streams.
+  const int kw0 = (int)((long)Kf * blockIdx.y / a.split), kw1 = (int)((long)Kf * (blockIdx.y + 1) / a.split);
+  const int nbuf = (kw1 - kw0) / U;  // the launcher picks U so that this is exact
+  const bf16x8 *Wb = (const bf16x8 *)a.W + ((long)blockIdx.x * R * Kf + kw0) * 64 + lane;
+  const bf16x8 *Ab = (const bf16x8 *)a.A + (long)kw0 * 64 + lane;
 
   floatx4 acc[R][MB];
 #pragma unroll
@@ -131,13 +133,13 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
     for (int m = 0; m < MB; ++m) acc[r][m] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   bf16x8 w0[U][R], x0[U][MB], w1[U][R], x1[U][MB];
-  auto load = [&](int kf, bf16x8(&w)[U][R], bf16x8(&x)[U][MB]) {
+  auto load = [&](int j, bf16x8(&w)[U][R], bf16x8(&x)[U][MB]) {  // j-th buffer of the workgroup
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) w[u][r] = Wb[((long)r * Kf + kf + u) * 64];
+      for (int r = 0; r < R; ++r) w[u][r] = Wb[((long)r * Kf + j * U + u) * 64];
 #pragma unroll
-      for (int m = 0; m < MB; ++m) x[u][m] = Ab[((long)m * Kf + kf + u) * 64];
+      for (int m = 0; m < MB; ++m) x[u][m] = Ab[((long)m * Kf + j * U + u) * 64];
     }
   };
   auto fma = [&](bf16x8(&w)[U][R], bf16x8(&x)[U][MB]) {
@@ -150,34 +152,23 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
           acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u][r], x[u][m], acc[r][m], 0, 0, 0);
   };
 
-  int kf = kf0;
-  const int nfull = (kf1 - kf0) / U;  // whole buffers
-  if (nfull > 0) {
-    load(kf, w0, x0);
-    int i = 0;
-    for (; i + 2 <= nfull; i += 2) {  // two buffers per trip
-      load(kf + U, w1, x1);
+  // two register buffers: the loads of one are in flight while the MFMAs of the other issue
+  int j = wave;
+  if (j < nbuf) {
+    load(j, w0, x0);
+    while (true) {
+      const int j1 = j + WAVES, j2 = j + 2 * WAVES;
+      if (j1 < nbuf) load(j1, w1, x1);
       fma(w0, x0);
-      if (i + 2 < nfull) load(kf + 2 * U, w0, x0);
+      if (j1 >= nbuf) break;
+      if (j2 < nbuf) load(j2, w0, x0);
       fma(w1, x1);
-      kf += 2 * U;
-    }
-    if (i < nfull) {  // odd buffer left; it was loaded into w0/x0
-      fma(w0, x0);
-      kf += U;
-    }
-  }
-  for (; kf < kf1; ++kf) {  // remainder k-steps (U == 2 only)
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const bf16x8 wv = Wb[((long)r * Kf + kf) * 64];
-#pragma unroll
-      for (int m = 0; m < MB; ++m)
-        acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, Ab[((long)m * Kf + kf) * 64], acc[r][m], 0, 0, 0);
+      if (j2 >= nbuf) break;
+      j = j2;
     }
   }
 
-  // sum the four waves' partial tiles in a fixed order (deterministic)
+  // sum the waves' partial tiles in a fixed order (deterministic)
 #pragma unroll
   for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -185,11 +176,17 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
   __syncthreads();
 
   if constexpr (EPI == EPI_LOGITS) {
-    __shared__ float cv[RM][16];
-    __shared__ int ci[RM][16];
-    for (int p = wave; p < RM; p += 4) {
-      floatx4 v = red[p * 64 + lane];
-      for (int w = 1; w < 4; ++w) v += red[(w * RM + p) * 64 + lane];
+    floatx4 v[(RM + WAVES - 1) / WAVES];
+    int np = 0;
+    for (int p = wave; p < RM; p += WAVES, ++np) {
+      v[np] = red[p * 64 + lane];
+      for (int w = 1; w < WAVES; ++w) v[np] += red[(w * RM + p) * 64 + lane];
+    }
+    __syncthreads();  // everyone has read its tiles: the buffer is reused for the argmax candidates
+    float *cv = (float *)red;             // [RM][16]
+    int *ci = (int *)red + RM * 16;       // [RM][16]
+    np = 0;
+    for (int p = wave; p < RM; p += WAVES, ++np) {
       const int r = p / MB, m = p % MB;
       const int b = m * 16 + (lane & 15);
       const int n0 = (blockIdx.x * R + r) * 16 + 4 * (lane >> 4);
@@ -197,8 +194,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
       int bi = 0x7fffffff;
       for (int i = 0; i < 4; ++i) {
         if (n0 + i < a.N) {
-          if (a.logits && b < a.B) a.logits[(long)b * a.N + n0 + i] = v[i];
-          if (v[i] > best) { best = v[i]; bi = n0 + i; }
+          if (a.logits && b < a.B) a.logits[(long)b * a.N + n0 + i] = v[np][i];
+          if (v[np][i] > best) { best = v[np][i]; bi = n0 + i; }
         }
       }
       for (int o = 16; o < 64; o <<= 1) {  // across the four 4-row groups of this column
@@ -206,25 +203,25 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
         const int oi = __shfl_xor(bi, o);
         if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
       }
-      if (lane < 16) { cv[p][lane] = best; ci[p][lane] = bi; }
+      if (lane < 16) { cv[p * 16 + lane] = best; ci[p * 16 + lane] = bi; }
     }
     __syncthreads();
     if (threadIdx.x < MB * 16) {
       const int m = threadIdx.x >> 4, c = threadIdx.x & 15;
-      float best = cv[m][c];
-      int bi = ci[m][c];
+      float best = cv[m * 16 + c];
+      int bi = ci[m * 16 + c];
       for (int r = 1; r < R; ++r) {
-        const float ov = cv[r * MB + m][c];
-        const int oi = ci[r * MB + m][c];
+        const float ov = cv[(r * MB + m) * 16 + c];
+        const int oi = ci[(r * MB + m) * 16 + c];
         if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
       }
       a.pmax[(long)blockIdx.x * a.B_pad + m * 16 + c] = best;
       a.pidx[(long)blockIdx.x * a.B_pad + m * 16 + c] = bi;
     }
   } else {
-    for (int p = wave; p < RM; p += 4) {
+    for (int p = wave; p < RM; p += WAVES) {
       floatx4 v = red[p * 64 + lane];
-      for (int w = 1; w < 4; ++w) v += red[(w * RM + p) * 64 + lane];
+      for (int w = 1; w < WAVES; ++w) v += red[(w * RM + p) * 64 + lane];
       const int r = p / MB, m = p % MB;
       gemm_epilogue<EPI>(a, m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
     }
@@ -233,48 +230,60 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
 
 int bf16_gemm_groups(int N, int R) { return (N + 16 * R - 1) / (16 * R); }
 
-template <int MB, int R, int U>
-static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid, size_t lds) {
+template <int MB, int R, int U, int WAVES>
+static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid) {
+  const size_t lds = (size_t)WAVES * R * MB * 64 * sizeof(floatx4);
+  const dim3 blk(WAVES * 64);
   switch (epi) {
-    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL, U>), grid, dim3(256), lds, s, a); break;
-    case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV, U>), grid, dim3(256), lds, s, a); break;
-    case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU, U>), grid, dim3(256), lds, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U>), grid, dim3(256), lds, s, a); break;
+    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL, U, WAVES>), grid, blk, lds, s, a); break;
+    case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV, U, WAVES>), grid, blk, lds, s, a); break;
+    case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU, U, WAVES>), grid, blk, lds, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a); break;
   }
+}
+template <int MB, int R, int U>
+static void launch_gemm_w(hipStream_t s, const GemmArgs &a, int epi, int waves, dim3 grid) {
+  // the cross-wave reduction buffer is WAVES * R * MB KiB of LDS; stay within 64 KiB
+  if constexpr (R * MB <= 8) {
+    if (waves >= 8) { launch_gemm_epi<MB, R, U, 8>(s, a, epi, grid); return; }
+  }
+  launch_gemm_epi<MB, R, U, 4>(s, a, epi, grid);
 }
 template <int MB, int R>
-static void launch_gemm_u(hipStream_t s, const GemmArgs &a, int epi, int U, dim3 grid, size_t lds) {
+static void launch_gemm_u(hipStream_t s, const GemmArgs &a, int epi, int U, int waves, dim3 grid) {
   // register budget: two buffers of U * (R + MB) fragments plus R * MB accumulators
   if constexpr ((R + MB) * 4 <= 24) {
-    if (U >= 4) { launch_gemm_epi<MB, R, 4>(s, a, epi, grid, lds); return; }
+    if (U >= 4) { launch_gemm_w<MB, R, 4>(s, a, epi, waves, grid); return; }
   }
   if constexpr ((R + MB) * 2 <= 24) {
-    if (U >= 2) { launch_gemm_epi<MB, R, 2>(s, a, epi, grid, lds); return; }
+    if (U >= 2) { launch_gemm_w<MB, R, 2>(s, a, epi, waves, grid); return; }
   }
-  launch_gemm_epi<MB, R, 1>(s, a, epi, grid, lds);
+  launch_gemm_w<MB, R, 1>(s, a, epi, waves, grid);
 }
 template <int MB>
-static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int U, dim3 grid) {
-  const size_t lds = (size_t)4 * R * MB * 64 * sizeof(floatx4);
-  if (R == 1) launch_gemm_u<MB, 1>(s, a, epi, U, grid, lds);
-  else if (R == 2) launch_gemm_u<MB, 2>(s, a, epi, U, grid, lds);
-  else launch_gemm_u<MB, 4>(s, a, epi, U, grid, lds);
+static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves, dim3 grid) {
+  if (R == 1) launch_gemm_u<MB, 1>(s, a, epi, U, waves, grid);
+  else if (R == 2) launch_gemm_u<MB, 2>(s, a, epi, U, waves, grid);
+  else launch_gemm_u<MB, 4>(s, a, epi, U, waves, grid);
 }
 
-// Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}; the
-// cross-wave reduction buffer (4 * R * MB KiB of LDS) caps R for wide batches.
-int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U) {
+// Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}.
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves) {
   const int MB = a.B_pad / 16;
   if (MB >= 8) R = 1;
   else if (MB >= 4 && R > 2) R = 2;
   if (R == 3) R = 2;
+  const int split = epi == EPI_LOGITS ? 1 : a.split;
+  const int Kf = a.K / 32;
+  if (Kf % split) return -1;            // equal K ranges per workgroup
+  while (U > 1 && (Kf / split) % U) U >>= 1;  // whole buffers only
   const int groups = bf16_gemm_groups(a.N, R);
-  const dim3 grid(groups, epi == EPI_LOGITS ? 1 : a.split);
+  const dim3 grid(groups, split);
   switch (MB) {
-    case 1: launch_gemm_r<1>(s, a, epi, R, U, grid); break;
-    case 2: launch_gemm_r<2>(s, a, epi, R, U, grid); break;
-    case 4: launch_gemm_r<4>(s, a, epi, R, U, grid); break;
-    case 8: launch_gemm_r<8>(s, a, epi, R, U, grid); break;
+    case 1: launch_gemm_r<1>(s, a, epi, R, U, waves, grid); break;
+    case 2: launch_gemm_r<2>(s, a, epi, R, U, waves, grid); break;
+    case 4: launch_gemm_r<4>(s, a, epi, R, U, waves, grid); break;
+    case 8: launch_gemm_r<8>(s, a, epi, R, U, waves, grid); break;
     default: return -1;
   }
   return groups;

@@ -41,7 +41,7 @@ struct LayerW {
 };
 
 struct GemmPlan {
-  int R = 1, split = 1, U = 2;
+  int R = 1, split = 1, U = 1, waves = 8;
 };
 
 }  // namespace
@@ -180,28 +180,30 @@ int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, lon
   return SKD_OK;
 }
 
-// Launch shapes.  Measured on MI355X at the OPT-6.7B widths (batch 32): the
-// kernels are insensitive to R / U within +-5 %, but want (a) a few hundred
-// workgroups so every CU streams, and (b) about 8 k-steps per wave when K is
-// split across workgroups.
+// Launch shapes.  Measured on MI355X at the OPT-6.7B widths (batch 32): 8
+// waves per workgroup interleaving k-steps, 64 weight rows per workgroup
+// (R = 4) and one k-step per register buffer stream best; every CU should get
+// work, and a wave should see about 8 k-steps when K is split across
+// workgroups.
 GemmPlan plan_direct(int N, int B_pad) {  // whole K inside the workgroup
   GemmPlan p;
-  const int rmax = B_pad >= 128 ? 1 : 2;
-  p.R = (rmax >= 2 && bf16_gemm_groups(N, 2) >= 256) ? 2 : 1;
+  const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
+  p.R = 1;
+  for (int R = rmax; R >= 1; R >>= 1)
+    if (bf16_gemm_groups(N, R) >= 192) { p.R = R; break; }
   p.split = 1;
-  p.U = 2;
   return p;
 }
 GemmPlan plan_split(int N, int K, int B_pad) {  // partial sums, reduced by the LayerNorm kernel
   GemmPlan p;
   const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
   const int Kf = K / 32;
-  int S = Kf / 32;
+  int S = Kf / 64;                       // 8 waves x 8 k-steps per workgroup
   S = S < 1 ? 1 : (S > 16 ? 16 : S);
+  while (S > 1 && Kf % S) --S;
   p.R = rmax;
   while (p.R > 1 && (N % (16 * p.R) || bf16_gemm_groups(N, p.R) * S < 256)) p.R >>= 1;
   p.split = S;
-  p.U = 1;
   return p;
 }
 
@@ -330,6 +332,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
     bf16_t *a = (bf16_t *)st->a, *q = (bf16_t *)st->q, *o = (bf16_t *)st->o, *u = (bf16_t *)st->u;
     const LayerW &w0 = st->lw[layers[0]];
     { ProfScope ps_(st, SKD_PROF_EMBED_LN); bf16_embed_ln(s, tokens_dev, st->start_dev, t, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, w0.ln1_g, w0.ln1_b, st->x, a, B, d, c.vocab); }
+    int grc = 0;
     for (int i = 0; i < n; ++i) {
       const int l = layers[i];
       const LayerW &w = st->lw[l];
@@ -338,19 +341,23 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       // q, k, v projection; k and v go straight into this layer's page slot for column t
       ga.W = (const bf16_t *)w.wqkv; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
       ga.q_out = q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
-      { ProfScope ps_(st, SKD_PROF_GEMM_QKV); bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U, st->p_qkv.waves); }
+      if (grc < 0) return SKD_ERR_SHAPE;
       AttnArgs aa{};
       aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
       aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
       ga.W = (const bf16_t *)w.wo; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
-      { ProfScope ps_(st, SKD_PROF_GEMM_OUT); bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R, st->p_out.U); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_OUT); grc = bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R, st->p_out.U, st->p_out.waves); }
+      if (grc < 0) return SKD_ERR_SHAPE;
       { ProfScope ps_(st, SKD_PROF_REDUCE_LN); bf16_reduce_ln(s, st->partial, st->p_out.split, st->B_pad, w.bo, st->x, w.ln2_g, w.ln2_b, a, B, d); }
       ga.W = (const bf16_t *)w.w1; ga.A = a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.split = 1; ga.act_out = u;
-      { ProfScope ps_(st, SKD_PROF_GEMM_FFN1); bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R, st->p_ffn1.U); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_FFN1); grc = bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R, st->p_ffn1.U, st->p_ffn1.waves); }
+      if (grc < 0) return SKD_ERR_SHAPE;
       ga.W = (const bf16_t *)w.w2; ga.A = u; ga.N = d; ga.K = f; ga.split = st->p_ffn2.split;
-      { ProfScope ps_(st, SKD_PROF_GEMM_FFN2); bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R, st->p_ffn2.U); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_FFN2); grc = bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R, st->p_ffn2.U, st->p_ffn2.waves); }
+      if (grc < 0) return SKD_ERR_SHAPE;
       // the reducer of the last sub-block already applies the next LayerNorm:
       // LayerNorm 1 of the next ACTIVE layer, or the final LayerNorm
       const float *ng = (i + 1 < n) ? st->lw[layers[i + 1]].ln1_g : st->lnf_g;
@@ -444,6 +451,8 @@ extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip
     ov("SKD_S_OUT", st->p_out.split, 1, 32); ov("SKD_S_FFN2", st->p_ffn2.split, 1, 32);
     ov("SKD_U_QKV", st->p_qkv.U, 1, 4); ov("SKD_U_FFN1", st->p_ffn1.U, 1, 4); ov("SKD_U_HEAD", st->p_head.U, 1, 4);
     ov("SKD_U_OUT", st->p_out.U, 1, 4); ov("SKD_U_FFN2", st->p_ffn2.U, 1, 4);
+    ov("SKD_W_QKV", st->p_qkv.waves, 4, 8); ov("SKD_W_FFN1", st->p_ffn1.waves, 4, 8); ov("SKD_W_HEAD", st->p_head.waves, 4, 8);
+    ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
     for (GemmPlan *p : {&st->p_qkv, &st->p_ffn1, &st->p_head, &st->p_out, &st->p_ffn2}) {
       if (p->R == 3) p->R = 2;
       if (Bp >= 128) p->R = 1; else if (Bp >= 64 && p->R > 2) p->R = 2;
@@ -575,7 +584,8 @@ extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logi
     ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
     ga.N = V; ga.K = d; ga.split = 1; ga.logits = logits_target; ga.pmax = st->pmax; ga.pidx = st->pidx;
     int groups = 0;
-    { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U); }
+    { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves); }
+    if (groups < 0) return SKD_ERR_SHAPE;
     { ProfScope ps_(st, SKD_PROF_ARGMAX); bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B); }
   }
   HIPCHECK(hipGetLastError());

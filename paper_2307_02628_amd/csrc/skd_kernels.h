@@ -66,9 +66,10 @@ struct GemmArgs {
   float *pmax;         // EPI_LOGITS: [groups][B_pad]
   int32_t *pidx;       // EPI_LOGITS
 };
-// R in {1,2,4}: 16-row weight tiles per wave; U in {1,2,4}: k-steps per register buffer (prefetch depth).
-// Returns the number of row groups launched (grid.x).
-int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U);
+// R in {1,2,4}: 16-row weight tiles per wave; U in {1,2,4}: k-steps per register buffer (prefetch depth);
+// waves in {4,8}: waves per workgroup.  K/32 must be a multiple of a.split.
+// Returns the number of row groups launched (grid.x), or -1 for an unsupported shape.
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U, int waves);
 int bf16_gemm_groups(int N, int R);
 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
