@@ -33,6 +33,9 @@ WORKLOADS = {
     "opt6.7b_b8_p2048_t512_32to12": (S.OPT_6_7B, 8, 2048, 512, 12, 32, None),
     "opt6.7b_b128_p64-512_t128_24to8": (S.OPT_6_7B, 128, 512, 128, 8, 24, (64, 512)),
     "tiny_b2_p16_t16_4to2": (S.TINY, 2, 16, 16, 2, 4, None),
+    # two layers of the 6.7B shape with the primary workload's batch and lengths: same per-launch kernel shapes,
+    # short enough for counter collection
+    "opt6.7b-2layers_b32_p512_t256_2to1": (S.ModelShape(2, 4096, 32, 16384, 50272, 3072), 32, 512, 256, 1, 2, None),
 }
 DEFAULT_WORKLOAD = "opt6.7b_b32_p512_t256_32to6"
 
