@@ -184,15 +184,18 @@ int skd_synchronize(skd_state *st);
 /* Copy the fp32 residual stream of the last processed column to host x_out [B][d]. */
 int skd_debug_read_hidden(skd_state *st, float *x_out);
 
-/* Declare columns 0..cols-1 processed with every token real, as if a prefill
- * of length `cols` (>= P is not required; cols <= N) had run, and set layer
- * caches from host arrays: for each layer l with Kin[l] != NULL, Kin[l] and
- * Vin[l] are [B][cols][d] fp32 and become that layer's cache (rounded to the
- * path's KV precision).  Layers with NULL entries are marked as holding
- * `cols` columns of zeros.  Used to set up single decode steps at long
- * contexts without running a long prompt.  Kin / Vin are host arrays of L
- * host pointers. */
-int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, const float *const *Vin);
+/* Declare columns 0..cols-1 processed (P <= cols < N), as if a prompt of that
+ * length had run, and set layer caches from host arrays: for each layer l with
+ * Kin[l] != NULL, Kin[l] and Vin[l] are [B][cols][d] fp32 and become that
+ * layer's cache (rounded to the path's KV precision); layers with NULL entries
+ * hold zeros.  Layers that leave the active window before column `cols` keep
+ * only what they reserved.  start [B] (may be NULL = no padding) gives each
+ * row's number of left-padding columns, 0 <= start[b] < cols.  Used to set up
+ * single decode steps at long contexts without running a long prompt.  Kin /
+ * Vin are host arrays of L host pointers.  Errors: SKD_ERR_NULL,
+ * SKD_ERR_RANGE, SKD_ERR_NOMEM, SKD_ERR_HIP. */
+int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, const float *const *Vin,
+                      const int32_t *start);
 
 /* Read back row b of layer l's cache: k_out, v_out [len][d] fp32 with
  * len = skd_kv_len(l). */

@@ -63,6 +63,7 @@ def _lib(real: str) -> C.CDLL:
         lib.ora_kv_len.argtypes = [C.c_void_p, C.c_int32]
         lib.ora_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         lib.ora_seek.argtypes = [C.c_void_p, C.c_int32]
+        lib.ora_seek_ragged.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         lib.ora_column.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                    C.c_void_p, C.c_void_p]
         lib.ora_recompute.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
@@ -176,8 +177,12 @@ class Decoder:
         assert K.shape == V.shape and K.shape[0] == self.B and K.shape[2] == self.shape.d
         _check(self._lib.ora_kv_load(self._h, layer, K.shape[1], K.ctypes.data, V.ctypes.data), "kv_load")
 
-    def seek(self, cols: int):
-        _check(self._lib.ora_seek(self._h, cols), "seek")
+    def seek(self, cols: int, start=None):
+        if start is None:
+            _check(self._lib.ora_seek(self._h, cols), "seek")
+        else:
+            st = np.ascontiguousarray(start, dtype=np.int32)
+            _check(self._lib.ora_seek_ragged(self._h, cols, st.ctypes.data), "seek_ragged")
 
     def column_rc(self, i: int, tokens, layers: Sequence[int], real_tok=None, want_logits: bool = True):
         tok = np.ascontiguousarray(tokens, dtype=np.int32)

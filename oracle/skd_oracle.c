@@ -298,6 +298,20 @@ int ora_seek(ora_state *st, int32_t cols) {
   return ORA_OK;
 }
 
+/* As ora_seek, with left padding: row b's columns 0..start[b]-1 are padding
+ * (never attended to, no position id). */
+int ora_seek_ragged(ora_state *st, int32_t cols, const int32_t *start) {
+  if (!st || !start) return ORA_ERR_NULL;
+  if (cols < 0 || cols > st->N) return ORA_ERR_RANGE;
+  for (int b = 0; b < st->B; ++b) {
+    if (start[b] < 0 || start[b] >= cols) return ORA_ERR_RANGE;
+    for (int j = 0; j < cols; ++j) st->valid[(size_t)b * st->N + j] = (uint8_t)(j >= start[b]);
+    st->n_real[b] = cols - start[b];
+  }
+  st->next_col = cols;
+  return ORA_OK;
+}
+
 /* Process column i for all B rows with the given ascending layer list.
  *   tokens[B]      input token of each row at column i
  *   real_tok[B]    1 = real token, 0 = padding (NULL = all real).  A padded

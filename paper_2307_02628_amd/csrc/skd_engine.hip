@@ -661,11 +661,15 @@ extern "C" int skd_debug_read_hidden(skd_state *st, float *x_out) {
   return SKD_OK;
 }
 
-extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, const float *const *Vin) {
+extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, const float *const *Vin,
+                                 const int32_t *start_in) {
   if (!st) return SKD_ERR_NULL;
   const skd_config &c = st->cfg;
   if (cols < c.prompt_size || cols >= c.sequence_length) return SKD_ERR_RANGE;
   const int B = c.batch, d = c.d_model;
+  if (start_in)
+    for (int b = 0; b < B; ++b)
+      if (start_in[b] < 0 || start_in[b] >= cols) return SKD_ERR_RANGE;
   const size_t n = (size_t)B * cols * d;
   float *kd = nullptr, *vd = nullptr;
   HIPCHECK(hipMalloc((void **)&kd, n * sizeof(float)));
@@ -694,6 +698,7 @@ extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const
   (void)hipFree(vd);
   if (rc != SKD_OK) return rc;
   std::vector<int32_t> start(B, 0);
+  if (start_in) start.assign(start_in, start_in + B);
   HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
   HIPCHECK(hipStreamSynchronize(st->stream));
   st->prefilled = true;

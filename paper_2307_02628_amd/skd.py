@@ -75,7 +75,7 @@ def lib() -> C.CDLL:
         l.skd_kv_pages_dense.restype = C.c_int64
         l.skd_synchronize.argtypes = [C.c_void_p]
         l.skd_debug_read_hidden.argtypes = [C.c_void_p, C.c_void_p]
-        l.skd_debug_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        l.skd_debug_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_debug_kv_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         l.skd_destroy.argtypes = [C.c_void_p]
         l.skd_destroy.restype = None
@@ -239,7 +239,7 @@ class Decoder:
         _check(self._lib.skd_debug_read_hidden(self._h, x.ctypes.data), "skd_debug_read_hidden")
         return x
 
-    def kv_load(self, cols: int, K: Sequence[Optional[np.ndarray]], V: Sequence[Optional[np.ndarray]]):
+    def kv_load(self, cols: int, K: Sequence[Optional[np.ndarray]], V: Sequence[Optional[np.ndarray]], start=None):
         keep = []
 
         def tab(lst):
@@ -255,7 +255,8 @@ class Decoder:
             return (C.c_void_p * self.cfg.L)(*ptrs)
 
         kt, vt = tab(K), tab(V)
-        _check(self._lib.skd_debug_kv_load(self._h, cols, kt, vt), "skd_debug_kv_load")
+        st = None if start is None else np.ascontiguousarray(start, dtype=np.int32)
+        _check(self._lib.skd_debug_kv_load(self._h, cols, kt, vt, _ptr_of(st)), "skd_debug_kv_load")
 
     def kv_read(self, layer: int, b: int):
         n = self.kv_len(layer)

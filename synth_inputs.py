@@ -21,6 +21,7 @@ were drawn before it.
 from __future__ import annotations
 
 import dataclasses
+import os
 from typing import Dict, List, Optional
 
 import numpy as np
@@ -50,17 +51,42 @@ _PER_LAYER = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo",
 _GLOBAL = ("tok_emb", "pos_emb", "lnf_g", "lnf_b")
 
 
-def _stream(seed: int, tensor_id: int) -> np.random.Generator:
-    return np.random.Generator(np.random.Philox(key=[int(seed), int(tensor_id)]))
+_CHUNK = 1 << 22          # elements per generator stream
+_POOL = None
+
+
+def _pool():
+    global _POOL
+    if _POOL is None:
+        import concurrent.futures
+        _POOL = concurrent.futures.ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1)))
+    return _POOL
+
+
+def _stream(seed: int, tensor_id: int, chunk: int = 0) -> np.random.Generator:
+    """Counter-based Philox stream keyed by (seed, tensor id, chunk index)."""
+    return np.random.Generator(np.random.Philox(key=[int(seed), (int(tensor_id) << 32) | int(chunk)]))
 
 
 def _normal(seed: int, tid: int, shape, std: float = 0.02, mean: float = 0.0) -> np.ndarray:
-    g = _stream(seed, tid)
-    out = g.standard_normal(size=shape, dtype=np.float32)
-    out *= np.float32(std)
-    if mean != 0.0:
-        out += np.float32(mean)
-    return out
+    """N(mean, std) fp32 tensor.  The flat tensor is cut into chunks of 2^22 elements, chunk c drawn from its own
+    Philox stream (seed, tid, c), so the values do not depend on the number of worker threads."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.float32)
+
+    def fill(c):
+        view = out[c * _CHUNK:(c + 1) * _CHUNK]
+        _stream(seed, tid, c).standard_normal(size=view.shape, dtype=np.float32, out=view)
+        view *= np.float32(std)
+        if mean != 0.0:
+            view += np.float32(mean)
+
+    nchunks = (n + _CHUNK - 1) // _CHUNK
+    if nchunks <= 1:
+        fill(0)
+    else:
+        list(_pool().map(fill, range(nchunks)))
+    return out.reshape(shape)
 
 
 def layer_tensor_shapes(s: ModelShape) -> Dict[str, tuple]:
@@ -97,13 +123,24 @@ def make_weights(s: ModelShape, seed: int = 0, layers: Optional[int] = None) -> 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bfloat16 (ties to even) and return them
-    again as fp32.  Used to hand the CPU oracle exactly the weight values the
-    bf16 device path stores."""
-    a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    u = (u + 0x7FFF + lsb) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    again as fp32 (a new array).  Used to hand the CPU oracle exactly the weight
+    values the bf16 device path stores."""
+    out = np.array(a, dtype=np.float32, order="C", copy=True)
+    flat = out.reshape(-1).view(np.uint32)
+
+    def rnd(c):
+        u = flat[c * _CHUNK:(c + 1) * _CHUNK]
+        lsb = (u >> np.uint32(16)) & np.uint32(1)
+        lsb += np.uint32(0x7FFF)
+        u += lsb                      # finite inputs cannot wrap around
+        u &= np.uint32(0xFFFF0000)
+
+    nchunks = (flat.size + _CHUNK - 1) // _CHUNK
+    if nchunks <= 1:
+        rnd(0)
+    else:
+        list(_pool().map(rnd, range(nchunks)))
+    return out
 
 
 def bf16_bits(a: np.ndarray) -> np.ndarray:
