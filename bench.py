@@ -237,10 +237,14 @@ def main():
                           for k, v in prof.items()}
         dom = max((k for k in prof if prof[k]["bytes"]), key=lambda k: prof[k]["ms"])
         ach = prof[dom]["bytes"] / (prof[dom]["ms"] * 1e-3) / 1e9
+        # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE: the ratio to the algorithmic bytes was
+        # measured per kernel on a 2-layer slice with the same launch shapes (profiles/pmc_traffic_*.md)
         traffic = None
-        tfile = os.path.join(ROOT, "profiles", f"traffic_{dom}_{args.workload}.json")
-        if os.path.exists(tfile):
-            traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+        tfile = os.path.join(ROOT, "profiles", "traffic_ratios_opt6.7b_b32.json")
+        if os.path.exists(tfile) and shape.d == 4096 and B == 32:
+            ratio = json.load(open(tfile))["kernels"].get(dom, {}).get("ratio")
+            if ratio:
+                traffic = ratio * prof[dom]["bytes"] / prof[dom]["launches"]
         roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_launch": prof[dom]["bytes"] / prof[dom]["launches"],
