@@ -264,6 +264,7 @@ template <int MB>
 static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves, dim3 grid) {
   if (R == 1) launch_gemm_u<MB, 1>(s, a, epi, U, waves, grid);
   else if (R == 2) launch_gemm_u<MB, 2>(s, a, epi, U, waves, grid);
+  else if (R == 3) launch_gemm_u<MB, 3>(s, a, epi, U, waves, grid);
   else launch_gemm_u<MB, 4>(s, a, epi, U, waves, grid);
 }
 
@@ -272,7 +273,6 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
   const int MB = a.B_pad / 16;
   if (MB >= 8) R = 1;
   else if (MB >= 4 && R > 2) R = 2;
-  if (R == 3) R = 2;
   const int split = epi == EPI_LOGITS ? 1 : a.split;
   const int Kf = a.K / 32;
   if (Kf % split) return -1;            // equal K ranges per workgroup

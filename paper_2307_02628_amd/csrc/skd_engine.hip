@@ -165,7 +165,7 @@ int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, lon
     prep_to_f32(st->stream, dsrc, w.elem == SKD_W_BF16, p, N * K);
     *out = p;
   } else if (frag) {
-    const long N_pad = (N + 63) / 64 * 64;  // whole 4-tile groups: the widest wave tile never leaves the buffer
+    const long N_pad = (N + 191) / 192 * 192;  // whole groups of 1..4 tiles: no wave tile ever leaves the buffer
     bf16_t *p = nullptr;
     SKDCHECK(dev_alloc(st, &p, (size_t)N_pad * K));
     prep_matrix_frag(st->stream, dsrc, w.elem == SKD_W_BF16, p, N, K, N_pad);
@@ -189,8 +189,8 @@ GemmPlan plan_direct(int N, int B_pad) {  // whole K inside the workgroup
   GemmPlan p;
   const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
   p.R = 1;
-  for (int R = rmax; R >= 1; R >>= 1)
-    if (bf16_gemm_groups(N, R) >= 192) { p.R = R; break; }
+  for (int R = rmax; R >= 1; --R)          // the largest R that still gives every CU a workgroup
+    if (bf16_gemm_groups(N, R) >= 256) { p.R = R; break; }
   p.split = 1;
   return p;
 }
@@ -459,7 +459,6 @@ extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip
     ov("SKD_W_QKV", st->p_qkv.waves, 4, 8); ov("SKD_W_FFN1", st->p_ffn1.waves, 4, 8); ov("SKD_W_HEAD", st->p_head.waves, 4, 8);
     ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
     for (GemmPlan *p : {&st->p_qkv, &st->p_ffn1, &st->p_head, &st->p_out, &st->p_ffn2}) {
-      if (p->R == 3) p->R = 2;
       if (Bp >= 128) p->R = 1; else if (Bp >= 64 && p->R > 2) p->R = 2;
     }
     st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
