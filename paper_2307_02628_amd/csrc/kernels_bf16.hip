@@ -112,6 +112,12 @@ __device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0,
   *(uint2 *)&a.act_out[d_frag_index(b, n0, a.N)] = pk;
 }
 
+// tile rows that fit the 64 KiB cross-wave reduction buffer at once (each tile row = WAVES * MB KiB)
+constexpr int gemm_stage_rows(int waves, int R, int MB) {
+  const int fit = 64 / (waves * MB);
+  return fit >= R ? R : (fit > 0 ? fit : 1);
+}
+
 template <int MB, int R, int EPI, int U, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
   constexpr int RM = R * MB;
@@ -168,7 +174,31 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
     }
   }
 
-  // sum the waves' partial tiles in a fixed order (deterministic)
+  // sum the waves' partial tiles in a fixed order (deterministic).  The LDS buffer holds RS of the R tile rows
+  // at a time (64 KiB at most), so wide batches reduce in stages.
+  constexpr int RS = gemm_stage_rows(WAVES, R, MB);
+  if constexpr (EPI != EPI_LOGITS) {
+#pragma unroll
+    for (int r0 = 0; r0 < R; r0 += RS) {
+      if (r0) __syncthreads();  // the previous stage has been consumed
+#pragma unroll
+      for (int rr = 0; rr < RS; ++rr)
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+          if (r0 + rr < R) red[(wave * (RS * MB) + rr * MB + m) * 64 + lane] = acc[r0 + rr < R ? r0 + rr : 0][m];
+      __syncthreads();
+      for (int p = wave; p < RS * MB; p += WAVES) {
+        const int r = r0 + p / MB, m = p % MB;
+        if (r < R) {
+          floatx4 v = red[p * 64 + lane];
+          for (int w = 1; w < WAVES; ++w) v += red[(w * (RS * MB) + p) * 64 + lane];
+          gemm_epilogue<EPI>(a, m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
+        }
+      }
+    }
+    return;
+  }
+  static_assert(EPI != EPI_LOGITS || RS == R, "the LM-head epilogue reduces in one stage");
 #pragma unroll
   for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -218,13 +248,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
       a.pmax[(long)blockIdx.x * a.B_pad + m * 16 + c] = best;
       a.pidx[(long)blockIdx.x * a.B_pad + m * 16 + c] = bi;
     }
-  } else {
-    for (int p = wave; p < RM; p += WAVES) {
-      floatx4 v = red[p * 64 + lane];
-      for (int w = 1; w < WAVES; ++w) v += red[(w * RM + p) * 64 + lane];
-      const int r = p / MB, m = p % MB;
-      gemm_epilogue<EPI>(a, m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
-    }
   }
 }
 
@@ -232,30 +255,30 @@ int bf16_gemm_groups(int N, int R) { return (N + 16 * R - 1) / (16 * R); }
 
 template <int MB, int R, int U, int WAVES>
 static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid) {
-  const size_t lds = (size_t)WAVES * R * MB * 64 * sizeof(floatx4);
+  const size_t lds = (size_t)WAVES * gemm_stage_rows(WAVES, R, MB) * MB * 64 * sizeof(floatx4);
   const dim3 blk(WAVES * 64);
   switch (epi) {
     case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL, U, WAVES>), grid, blk, lds, s, a); break;
     case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV, U, WAVES>), grid, blk, lds, s, a); break;
     case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU, U, WAVES>), grid, blk, lds, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a); break;
+    default:
+      if constexpr (gemm_stage_rows(WAVES, R, MB) == R)
+        hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a);
+      break;
   }
 }
 template <int MB, int R, int U>
 static void launch_gemm_w(hipStream_t s, const GemmArgs &a, int epi, int waves, dim3 grid) {
-  // the cross-wave reduction buffer is WAVES * R * MB KiB of LDS; stay within 64 KiB
-  if constexpr (R * MB <= 8) {
-    if (waves >= 8) { launch_gemm_epi<MB, R, U, 8>(s, a, epi, grid); return; }
-  }
-  launch_gemm_epi<MB, R, U, 4>(s, a, epi, grid);
+  if (waves >= 8) launch_gemm_epi<MB, R, U, 8>(s, a, epi, grid);
+  else launch_gemm_epi<MB, R, U, 4>(s, a, epi, grid);
 }
 template <int MB, int R>
 static void launch_gemm_u(hipStream_t s, const GemmArgs &a, int epi, int U, int waves, dim3 grid) {
-  // register budget: two buffers of U * (R + MB) fragments plus R * MB accumulators
-  if constexpr ((R + MB) * 4 <= 24) {
+  // register budget: R * MB accumulators plus two buffers of U * (R + MB) fragments, 4 VGPRs each
+  if constexpr (R * MB + 2 * 4 * (R + MB) <= 56) {
     if (U >= 4) { launch_gemm_w<MB, R, 4>(s, a, epi, waves, grid); return; }
   }
-  if constexpr ((R + MB) * 2 <= 24) {
+  if constexpr (R * MB + 2 * 2 * (R + MB) <= 56) {
     if (U >= 2) { launch_gemm_w<MB, R, 2>(s, a, epi, waves, grid); return; }
   }
   launch_gemm_w<MB, R, 1>(s, a, epi, waves, grid);
@@ -271,8 +294,10 @@ static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int 
 // Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}.
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves) {
   const int MB = a.B_pad / 16;
-  if (MB >= 8) R = 1;
-  else if (MB >= 4 && R > 2) R = 2;
+  if (R < 1 || R > 4 || (waves != 4 && waves != 8) || MB < 1 || MB > 8) return -1;
+  // the LM-head epilogue keeps all tile rows of the workgroup in the 64 KiB reduction buffer (the caller sizes
+  // its argmax partials by R, so R is never changed here)
+  if (epi == EPI_LOGITS && waves * R * MB > 64) return -1;
   const int split = epi == EPI_LOGITS ? 1 : a.split;
   const int Kf = a.K / 32;
   if (Kf % split) return -1;            // equal K ranges per workgroup

@@ -180,30 +180,36 @@ int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, lon
   return SKD_OK;
 }
 
-// Launch shapes.  Measured on MI355X at the OPT-6.7B widths (batch 32): 8
-// waves per workgroup interleaving k-steps, 64 weight rows per workgroup
-// (R = 4) and one k-step per register buffer stream best; every CU should get
-// work, and a wave should see about 8 k-steps when K is split across
-// workgroups.
+// Launch shapes.  Measured on MI355X at the OPT-6.7B widths: up to batch 64, 8
+// waves per workgroup interleaving k-steps with 48-64 weight rows per workgroup
+// and one k-step per register buffer stream best; at batch 128 the 4 x 8 tile
+// accumulators need the whole register file, so workgroups have 4 waves.
+// Every CU should get a workgroup; when K is split across workgroups a wave
+// should still see at least 2 k-steps.
+int plan_waves(int B_pad) { return B_pad >= 128 ? 4 : 8; }
 GemmPlan plan_direct(int N, int B_pad) {  // whole K inside the workgroup
   GemmPlan p;
-  const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
+  p.waves = plan_waves(B_pad);
   p.R = 1;
-  for (int R = rmax; R >= 1; --R)          // the largest R that still gives every CU a workgroup
+  for (int R = 4; R >= 1; --R)  // the largest R that still gives every CU a workgroup
     if (bf16_gemm_groups(N, R) >= 256) { p.R = R; break; }
   p.split = 1;
   return p;
 }
 GemmPlan plan_split(int N, int K, int B_pad) {  // partial sums, reduced by the LayerNorm kernel
   GemmPlan p;
-  const int rmax = B_pad >= 128 ? 1 : (B_pad >= 64 ? 2 : 4);
+  p.waves = plan_waves(B_pad);
   const int Kf = K / 32;
-  int S = Kf / 64;                       // 8 waves x 8 k-steps per workgroup
-  S = S < 1 ? 1 : (S > 16 ? 16 : S);
-  while (S > 1 && Kf % S) --S;
-  p.R = rmax;
-  while (p.R > 1 && (N % (16 * p.R) || bf16_gemm_groups(N, p.R) * S < 256)) p.R >>= 1;
-  p.split = S;
+  p.R = 4;
+  while (p.R > 1 && N % (16 * p.R)) --p.R;
+  for (;;) {
+    int S = 1;
+    while (S < 16 && bf16_gemm_groups(N, p.R) * S < 256 && Kf % (2 * S) == 0 && Kf / (2 * S) >= 2 * p.waves) S *= 2;
+    p.split = S;
+    if (bf16_gemm_groups(N, p.R) * S >= 256 || p.R == 1) break;
+    --p.R;
+    while (p.R > 1 && N % (16 * p.R)) --p.R;
+  }
   return p;
 }
 
@@ -458,9 +464,8 @@ extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip
     ov("SKD_U_OUT", st->p_out.U, 1, 4); ov("SKD_U_FFN2", st->p_ffn2.U, 1, 4);
     ov("SKD_W_QKV", st->p_qkv.waves, 4, 8); ov("SKD_W_FFN1", st->p_ffn1.waves, 4, 8); ov("SKD_W_HEAD", st->p_head.waves, 4, 8);
     ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
-    for (GemmPlan *p : {&st->p_qkv, &st->p_ffn1, &st->p_head, &st->p_out, &st->p_ffn2}) {
-      if (Bp >= 128) p->R = 1; else if (Bp >= 64 && p->R > 2) p->R = 2;
-    }
+    while (st->p_head.R > 1 && st->p_head.waves * st->p_head.R * (Bp / 16) > 64) --st->p_head.R;  // LM-head epilogue: one reduction stage
+    if (st->p_head.waves * st->p_head.R * (Bp / 16) > 64) st->p_head.waves = 4;
     st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
     // split the key range of one head over several workgroups only when rows*heads alone cannot fill the chip
     int splits = 1;
