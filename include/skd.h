@@ -55,7 +55,7 @@ typedef struct skd_state skd_state; /* opaque: device weights, KV pages, workspa
 typedef struct {
   /* model shape */
   int32_t L;        /* num_decoder_layers                                   */
-  int32_t d_model;  /* multiple of n_heads; bf16 path: head_dim 64 or 128   */
+  int32_t d_model;  /* multiple of n_heads; bf16 path: head_dim 64 or 128, d_model <= 16384 */
   int32_t n_heads;
   int32_t ffn;      /* FFN width; bf16 path: d_model and ffn multiples of 32 */
   int32_t vocab;

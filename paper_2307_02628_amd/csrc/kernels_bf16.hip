@@ -314,89 +314,100 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
   return groups;
 }
 
-// ------------------------------------------------------------------ embedding + first LayerNorm
-__global__ __launch_bounds__(256) void k_embed_ln(const int32_t *tokens, const int32_t *start, int t,
-                                                  const bf16_t *tok_emb, const bf16_t *pos_emb, const float *g,
-                                                  const float *bt, float *x, bf16_t *a_out, int d, int V) {
-  extern __shared__ float row[];
-  __shared__ float sh[4];
-  const int b = blockIdx.x;
+// ------------------------------------------------------------------ row kernels: embedding / split-K reduce, + LayerNorm
+// One 1024-thread workgroup per batch row.  These kernels move < 5 MB and are
+// pure latency chains, so each thread keeps its share of the row in registers
+// (float4 chunk c = threadIdx.x + 1024 * i, rows up to 16384 wide), issues
+// every global load it will ever need up front, and the row never touches LDS.
+constexpr int LN_NC = 4;
+
+// v[i] = elements 4c .. 4c+3 of row b.  LayerNorm (mean, biased variance, eps 1e-5) -> bf16 fragment-major row.
+__device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&gv)[LN_NC], const floatx4 (&bv)[LN_NC],
+                                     int d, int b, bf16_t *a_out, float *sh) {
+  const int d4 = d >> 2;
+  float s = 0;
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i)
+    if ((int)threadIdx.x + 1024 * i < d4) s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+  const float mean = block_sum_f(s, sh) / d;
+  float q = 0;
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i)
+    if ((int)threadIdx.x + 1024 * i < d4) {
+      const floatx4 t = v[i] - mean;
+      q += (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]);
+    }
+  const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i) {
+    const int c = (int)threadIdx.x + 1024 * i;
+    if (c < d4) {
+      const floatx4 y = (v[i] - mean) * rstd * gv[i] + bv[i];
+      *(uint2 *)&a_out[d_frag_index(b, 4 * c, d)] = make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
+    }
+  }
+}
+
+__global__ __launch_bounds__(1024) void k_embed_ln(const int32_t *tokens, const int32_t *start, int t,
+                                                   const bf16_t *tok_emb, const bf16_t *pos_emb, const float *g,
+                                                   const float *bt, float *x, bf16_t *a_out, int d, int V) {
+  __shared__ float sh[16];
+  const int b = blockIdx.x, d4 = d >> 2;
   int tok = tokens[b];
   tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
   int pos = t - start[b];  // number of real tokens before this column
   if (pos < 0) pos = 0;    // padding column, never attended to
-  float s = 0;
-  for (int k = threadIdx.x; k < d; k += 256) {
-    const float v = bf2f(tok_emb[(long)tok * d + k]) + bf2f(pos_emb[(long)pos * d + k]);
-    row[k] = v;
-    x[(long)b * d + k] = v;
-    s += v;
-  }
-  const float mean = block_sum_f(s, sh) / d;
-  float q = 0;
-  for (int k = threadIdx.x; k < d; k += 256) q += (row[k] - mean) * (row[k] - mean);
-  const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
-  for (int k8 = threadIdx.x; k8 < d / 8; k8 += 256) {
-    uint32_t pk[4];
-    for (int j = 0; j < 4; ++j) {
-      const int k = k8 * 8 + 2 * j;
-      pk[j] = pack2((row[k] - mean) * rstd * g[k] + bt[k], (row[k + 1] - mean) * rstd * g[k + 1] + bt[k + 1]);
+  const uint2 *te = (const uint2 *)(tok_emb + (long)tok * d), *pe = (const uint2 *)(pos_emb + (long)pos * d);
+  floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i) {
+    const int c = (int)threadIdx.x + 1024 * i;
+    if (c < d4) {
+      const uint2 a = te[c], p = pe[c];
+      gv[i] = ((const floatx4 *)g)[c];
+      bv[i] = ((const floatx4 *)bt)[c];
+      v[i] = floatx4{bf2f(a.x & 0xffffu) + bf2f(p.x & 0xffffu), bf2f(a.x >> 16) + bf2f(p.x >> 16),
+                     bf2f(a.y & 0xffffu) + bf2f(p.y & 0xffffu), bf2f(a.y >> 16) + bf2f(p.y >> 16)};
+      ((floatx4 *)x)[(long)b * d4 + c] = v[i];
     }
-    *(uint32x4 *)&a_out[d_frag_index(b, k8 * 8, d)] = uint32x4{pk[0], pk[1], pk[2], pk[3]};
   }
+  ln_finish_row(v, gv, bv, d, b, a_out, sh);
 }
 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
                    const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
                    int V) {
-  hipLaunchKernelGGL(k_embed_ln, dim3(B), dim3(256), d * sizeof(float), s, tokens, start, t, tok_emb, pos_emb, g, b,
-                     x, a_out, d, V);
+  hipLaunchKernelGGL(k_embed_ln, dim3(B), dim3(1024), 0, s, tokens, start, t, tok_emb, pos_emb, g, b, x, a_out, d, V);
 }
 
-// ------------------------------------------------------------------ split-K reduce + bias + residual + LayerNorm
-// One 1024-thread workgroup per batch row; each thread owns float4 chunks of
-// the row and issues all of its partial-sum loads before using any of them
-// (the kernel is a dependent-latency chain otherwise: it moves < 1 MB).
+// x[b][:] += bias + sum_s partial[s][b][:] (fixed order), then LayerNorm
 __global__ __launch_bounds__(1024) void k_reduce_ln(const float *partial, int split, int B_pad, const float *bias,
                                                     float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
-  extern __shared__ float row[];
   __shared__ float sh[16];
   const int b = blockIdx.x, d4 = d >> 2;
   const floatx4 *p4 = (const floatx4 *)partial;
   floatx4 *x4 = (floatx4 *)x + (long)b * d4;
-  const floatx4 *bias4 = (const floatx4 *)bias;
-  float s = 0;
-  for (int c = threadIdx.x; c < d4; c += 1024) {
-    floatx4 xv = x4[c], bv = bias4[c];
-    floatx4 v = p4[(long)b * d4 + c];
+  floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i) {
+    const int c = (int)threadIdx.x + 1024 * i;
+    if (c < d4) {
+      const floatx4 xv = x4[c], bias4 = ((const floatx4 *)bias)[c];
+      gv[i] = ((const floatx4 *)g)[c];
+      bv[i] = ((const floatx4 *)bt)[c];
+      floatx4 acc = p4[(long)b * d4 + c];
 #pragma unroll 8
-    for (int sp = 1; sp < split; ++sp) v += p4[((long)sp * B_pad + b) * d4 + c];  // fixed order
-    v = xv + (v + bv);
-    x4[c] = v;
-    *(floatx4 *)&row[4 * c] = v;
-    s += (v[0] + v[1]) + (v[2] + v[3]);
-  }
-  const float mean = block_sum_f(s, sh) / d;
-  float q = 0;
-  for (int c = threadIdx.x; c < d4; c += 1024) {
-    const floatx4 v = *(floatx4 *)&row[4 * c] - mean;
-    q += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
-  }
-  const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
-  for (int k8 = threadIdx.x; k8 < d / 8; k8 += 1024) {
-    uint32_t pk[4];
-    for (int j = 0; j < 4; ++j) {
-      const int k = k8 * 8 + 2 * j;
-      pk[j] = pack2((row[k] - mean) * rstd * g[k] + bt[k], (row[k + 1] - mean) * rstd * g[k + 1] + bt[k + 1]);
+      for (int sp = 1; sp < split; ++sp) acc += p4[((long)sp * B_pad + b) * d4 + c];
+      v[i] = xv + (acc + bias4);
+      x4[c] = v[i];
     }
-    *(uint32x4 *)&a_out[d_frag_index(b, k8 * 8, d)] = uint32x4{pk[0], pk[1], pk[2], pk[3]};
   }
+  ln_finish_row(v, gv, bv, d, b, a_out, sh);
 }
 
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d) {
-  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(1024), d * sizeof(float), s, partial, split, B_pad, bias, x, g, b,
-                     a_out, d);
+  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(1024), 0, s, partial, split, B_pad, bias, x, g, b, a_out, d);
 }
 
 // ------------------------------------------------------------------ decode attention over the paged KV cache

@@ -125,7 +125,7 @@ int check_config(const skd_config &c) {
   if (c.dtype == SKD_BF16) {
     const int dh = c.d_model / c.n_heads;
     if (dh != 64 && dh != 128) return SKD_ERR_SHAPE;
-    if (c.d_model % 32 || c.ffn % 32) return SKD_ERR_SHAPE;
+    if (c.d_model % 32 || c.ffn % 32 || c.d_model > 16384) return SKD_ERR_SHAPE;
     if (c.batch > 128) return SKD_ERR_SHAPE;
   }
   return SKD_OK;
