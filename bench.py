@@ -73,11 +73,11 @@ def class_bytes(shape, cls, sum_len):
             "lm_head": 2 * V * d, "attention": 2 * 2 * d * sum_len}.get(cls, 0)
 
 
-def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, profile):
+def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, profile, page_tokens=0):
     """Create a state, prefill, warm up, rewind, time `steps` decode steps.  Returns timing dict."""
     N = P + T
     stream = torch.cuda.Stream()
-    cfg = skd.make_config(shape, B, P, N, n_min, n_max, dtype=skd.BF16, io_on_device=1)
+    cfg = skd.make_config(shape, B, P, N, n_min, n_max, dtype=skd.BF16, io_on_device=1, page_tokens=page_tokens)
     g = torch.Generator(device="cpu")
     g.manual_seed(1)
     prompts = torch.randint(0, shape.V, (P, B), generator=g, dtype=torch.int32).cuda()      # [P][B]
@@ -173,6 +173,7 @@ def main():
     ap.add_argument("--no-full-depth", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--page-tokens", type=int, default=0, help="KV page size in tokens (0 = library default)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run a plain 1 GiB device copy 4 times (reference kernel of known traffic for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -204,10 +205,10 @@ def main():
     if ragged:
         mask = S.make_ragged_mask(B, P, ragged[0], ragged[1], seed=2)
     w = device_weights(shape, 0)
-    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile)
+    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile, args.page_tokens)
     full = None
     if not args.no_full_depth:
-        full = run_generation(skd, torch, shape, w, B, P, T, shape.L, shape.L, mask, steps, args.warmup, False)
+        full = run_generation(skd, torch, shape, w, B, P, T, shape.L, shape.L, mask, steps, args.warmup, False, args.page_tokens)
     del w
     torch.cuda.empty_cache()
 
