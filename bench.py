@@ -26,8 +26,12 @@ import synth_inputs as S  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 
+# Table 2 of the paper: (warm-up layers, min layer, max layer) per target speed-up
+TABLE2 = {"opt6.7b": {2: (1, 11, 22), 3: (1, 8, 14), 4: (1, 6, 10), 5: (1, 5, 8)},
+          "opt1.3b": {2: (1, 8, 16), 3: (1, 6, 10), 4: (1, 5, 7), 5: (1, 4, 6)}}
+
 WORKLOADS = {
-    # name: (shape, B, P, T, n_min, n_max, ragged prompt lengths or None)
+    # name: (shape, B, P, T, n_min, n_max, ragged prompt lengths or None[, warm-up layers])
     "opt1.3b_b16_p256_t256_24to12": (S.OPT_1_3B, 16, 256, 256, 12, 24, None),
     "opt6.7b_b32_p512_t256_32to6": (S.OPT_6_7B, 32, 512, 256, 6, 32, None),
     "opt6.7b_b8_p2048_t512_32to12": (S.OPT_6_7B, 8, 2048, 512, 12, 32, None),
@@ -37,6 +41,10 @@ WORKLOADS = {
     # short enough for counter collection
     "opt6.7b-2layers_b32_p512_t256_2to1": (S.ModelShape(2, 4096, 32, 16384, 50272, 3072), 32, 512, 256, 1, 2, None),
 }
+for _x, (_w, _lo, _hi) in TABLE2["opt6.7b"].items():   # the paper's presets at the primary workload's batch and lengths
+    WORKLOADS[f"opt6.7b_b32_p512_t256_table2-{_x}x"] = (S.OPT_6_7B, 32, 512, 256, _lo, _hi, None, _w)
+for _x, (_w, _lo, _hi) in TABLE2["opt1.3b"].items():
+    WORKLOADS[f"opt1.3b_b16_p256_t256_table2-{_x}x"] = (S.OPT_1_3B, 16, 256, 256, _lo, _hi, None, _w)
 DEFAULT_WORKLOAD = "opt6.7b_b32_p512_t256_32to6"
 
 
@@ -73,11 +81,13 @@ def class_bytes(shape, cls, sum_len):
             "lm_head": 2 * V * d, "attention": 2 * 2 * d * sum_len}.get(cls, 0)
 
 
-def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, profile, page_tokens=0):
+def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, profile, page_tokens=0,
+                   warmup_layers=0):
     """Create a state, prefill, warm up, rewind, time `steps` decode steps.  Returns timing dict."""
     N = P + T
     stream = torch.cuda.Stream()
-    cfg = skd.make_config(shape, B, P, N, n_min, n_max, dtype=skd.BF16, io_on_device=1, page_tokens=page_tokens)
+    cfg = skd.make_config(shape, B, P, N, n_min, n_max, warmup_layers, dtype=skd.BF16, io_on_device=1,
+                          page_tokens=page_tokens)
     g = torch.Generator(device="cpu")
     g.manual_seed(1)
     prompts = torch.randint(0, shape.V, (P, B), generator=g, dtype=torch.int32).cuda()      # [P][B]
@@ -198,14 +208,15 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    shape, B, P, T, n_min, n_max, ragged = WORKLOADS[args.workload]
+    shape, B, P, T, n_min, n_max, ragged, *rest = WORKLOADS[args.workload]
+    wl = rest[0] if rest else 0
     steps = args.steps if args.steps > 0 else T
     steps = min(steps, T)
     mask = None
     if ragged:
         mask = S.make_ragged_mask(B, P, ragged[0], ragged[1], seed=2)
     w = device_weights(shape, 0)
-    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile, args.page_tokens)
+    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile, args.page_tokens, wl)
     full = None
     if not args.no_full_depth:
         full = run_generation(skd, torch, shape, w, B, P, T, shape.L, shape.L, mask, steps, args.warmup, False, args.page_tokens)
@@ -220,7 +231,8 @@ def main():
         "ms_per_step": skip["ms"] / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "prompt": P, "decode_steps": T,
-                   "schedule": f"linear {n_max}->{n_min} of {shape.L} layers", "sum_n": int(sum(skip["layers"]))},
+                   "schedule": f"linear {n_max}->{n_min} of {shape.L} layers" + (f", {wl} warm-up" if wl else ""),
+                   "sum_n": int(sum(skip["layers"]))},
         "hbm_gbs": gbs, "hbm_frac_of_8TBs": gbs / HBM_PEAK_GBS,
         "algorithmic_gb_per_step": skip["bytes"] / steps / 1e9,
         "prefill_s": skip["prefill_s"],

@@ -32,13 +32,16 @@ CASES = {
     "cfg3_opt6.7b_b32": (S.OPT_6_7B, 32, 512, 768, 6, 32, 640, None, [0, 13, 31]),
     "cfg4_opt6.7b_b8_long": (S.OPT_6_7B, 8, 2048, 2560, 12, 32, 2301, None, [0, 5]),
     "cfg5_opt6.7b_b128_ragged": (S.OPT_6_7B, 128, 512, 640, 8, 24, 575, (64, 512), [0, 77, 127]),
+    # Table 2 preset "2x" of the 32-layer model: one warm-up layer, 22 -> 11 layers
+    "table2_2x_opt6.7b_b32_warmup1": (S.OPT_6_7B, 32, 512, 768, 11, 22, 650, None, [3, 30], 1),
 }
 
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name", sorted(CASES))
 def test_full_size_sampled_rows(name):
-    shape, B, P, N, n_min, n_max, t0, ragged, rows = CASES[name]
+    shape, B, P, N, n_min, n_max, t0, ragged, rows, *rest = CASES[name]
+    warm = rest[0] if rest else 0
     w = _aliased_weights(shape, 2, seed=21)
     g = np.random.Generator(np.random.Philox(key=[22, 0]))
     K = S.round_to_bf16(g.standard_normal(size=(B, t0, shape.d), dtype=np.float32))   # what a bf16 cache can hold
@@ -49,9 +52,11 @@ def test_full_size_sampled_rows(name):
         mask = S.make_ragged_mask(B, P, ragged[0], ragged[1], seed=2)
         start = (mask == 0).sum(axis=1).astype(np.int32)
         assert start.max() > 300 and start.min() < 100
-    cfg = skd.make_config(shape, B, P, N, n_min, n_max, dtype=skd.BF16)
+    cfg = skd.make_config(shape, B, P, N, n_min, n_max, warm, dtype=skd.BF16)
     sets = [skd.skd_active_layers(t0 + j, cfg) for j in range(2)]
-    assert sets[0] == O.active_layers(t0, P, N, n_min, n_max, 0, shape.L)
+    assert sets[0] == O.active_layers(t0, P, N, n_min, n_max, warm, shape.L)
+    if warm:
+        assert sets[0][:warm] == list(range(warm)) and sets[0][warm] > warm      # bottom warm-up layers + top window
 
     got = []
     with skd.Decoder(cfg, w) as dec:
