@@ -125,6 +125,23 @@ int skd_active_layers(int32_t t, const skd_config *cfg, int32_t *layers_out);
  * above, unknown enum); SKD_ERR_NOMEM; SKD_ERR_HIP. */
 int skd_create(const skd_config *cfg, const skd_weights *w, void *hip_stream, skd_state **out);
 
+/* As skd_create, with the layer count of EVERY position supplied by the caller
+ * instead of the linear decay: n_table[i], i = 0..N-1 (the paper leaves the
+ * decay function open: power law, Section 2.3 / Section 5; decay that already
+ * starts inside the prompt, Section 5).  The table must be non-increasing
+ * (SKD_ERR_SCHEDULE otherwise: a layer that re-enters would miss keys, Section
+ * 2.2), with 1 <= n_table[i] <= L (SKD_ERR_RANGE) and n_table[i] >= warmup
+ * (SKD_ERR_SHAPE).  n_min / n_max of cfg must still be valid but are not used;
+ * prefill processes prompt column i with n_table[i] layers.  The active set
+ * keeps its shape: `warmup` bottom layers plus the top n - warmup. */
+int skd_create_with_schedule(const skd_config *cfg, const skd_weights *w, void *hip_stream,
+                             const int32_t *n_table, skd_state **out);
+
+/* Active layers of this state at position t (0 <= t < N), ascending, into
+ * layers_out[0..L); returns their number.  Equals skd_active_layers for states
+ * made by skd_create. */
+int skd_state_active_layers(const skd_state *st, int32_t t, int32_t *layers_out);
+
 /* Process the prompt: columns 0..P-1, every one through all L layers
  * (Section 2.3: the prompt uses the full network), filling every layer's KV
  * cache.  tokens [B][P] int32 row-major.  attn_mask [B][P] uint8, 1 = real

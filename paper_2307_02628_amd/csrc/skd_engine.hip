@@ -87,6 +87,7 @@ struct skd_state {
   bool prefilled = false, have_hidden = false, have_argmax = false;
   int steps_done = 0;
   std::vector<int32_t> layers_tmp;
+  std::vector<int32_t> n_table;    // caller-supplied layer counts per position (empty = the linear schedule)
   // per-kernel timing (off by default)
   bool profiling = false;
   struct ProfRec { int cls; hipEvent_t a, b; };
@@ -213,6 +214,20 @@ GemmPlan plan_split(int N, int K, int B_pad) {  // partial sums, reduced by the 
   return p;
 }
 
+// Active layers at position t for this state: the linear schedule of the
+// configuration, or the caller's table (same shape of the set: warm-up layers
+// at the bottom, the rest of the budget at the top).
+int state_active_layers(const skd_state *st, int t, int32_t *out) {
+  const skd_config &c = st->cfg;
+  if (st->n_table.empty()) return skd_active_layers(t, &c, out);
+  if (t < 0 || t >= c.sequence_length) return SKD_ERR_RANGE;
+  const int n = st->n_table[t];
+  int k = 0;
+  for (int l = 0; l < c.warmup; ++l) out[k++] = l;
+  for (int l = c.L - (n - c.warmup); l < c.L; ++l) out[k++] = l;
+  return k;
+}
+
 int build_kv(skd_state *st) {
   const skd_config &c = st->cfg;
   const int pt = c.page_tokens ? c.page_tokens : 64;
@@ -224,10 +239,10 @@ int build_kv(skd_state *st) {
   g.page_elems = 2L * pt * c.d_model;
   // Static policy: the columns at which each layer runs are known before
   // generation starts, so each layer reserves exactly what it will hold.
-  st->kv_cap.assign(c.L, c.prompt_size);
+  st->kv_cap.assign(c.L, 0);
   std::vector<int32_t> act(c.L);
-  for (int t = c.prompt_size; t < c.sequence_length; ++t) {
-    const int n = skd_active_layers(t, &c, act.data());
+  for (int t = 0; t < c.sequence_length; ++t) {
+    const int n = state_active_layers(st, t, act.data());
     if (n < 0) return n;
     for (int i = 0; i < n; ++i) {
       if (st->kv_cap[act[i]] != t) return SKD_ERR_SCHEDULE;  // a layer re-entered: its cache would have a hole
@@ -385,10 +400,18 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
 
 }  // namespace
 
-extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip_stream, skd_state **out) {
+static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_stream, const int32_t *n_table,
+                       skd_state **out) {
   if (!cfg || !w || !out) return SKD_ERR_NULL;
   *out = nullptr;
   SKDCHECK(check_config(*cfg));
+  if (n_table) {  // monotone, within [max(1, warmup), L]
+    for (int i = 0; i < cfg->sequence_length; ++i) {
+      if (n_table[i] < 1 || n_table[i] > cfg->L) return SKD_ERR_RANGE;
+      if (n_table[i] < cfg->warmup) return SKD_ERR_SHAPE;
+      if (i && n_table[i] > n_table[i - 1]) return SKD_ERR_SCHEDULE;
+    }
+  }
   if ((w->location != SKD_HOST && w->location != SKD_DEVICE) || (w->elem != SKD_W_FP32 && w->elem != SKD_W_BF16))
     return SKD_ERR_SHAPE;
   if (!w->tok_emb || !w->pos_emb || !w->lnf_g || !w->lnf_b || !w->ln1_g || !w->ln1_b || !w->wqkv || !w->bqkv ||
@@ -401,6 +424,7 @@ extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip
     return rc;
   };
   st->cfg = *cfg;
+  if (n_table) st->n_table.assign(n_table, n_table + cfg->sequence_length);
   if (!st->cfg.page_tokens) st->cfg.page_tokens = 64;
   st->stream = (hipStream_t)hip_stream;
   st->bf16 = cfg->dtype == SKD_BF16;
@@ -497,6 +521,21 @@ extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip
   return SKD_OK;
 }
 
+extern "C" int skd_create(const skd_config *cfg, const skd_weights *w, void *hip_stream, skd_state **out) {
+  return create_impl(cfg, w, hip_stream, nullptr, out);
+}
+
+extern "C" int skd_create_with_schedule(const skd_config *cfg, const skd_weights *w, void *hip_stream,
+                                        const int32_t *n_table, skd_state **out) {
+  if (!n_table) return SKD_ERR_NULL;
+  return create_impl(cfg, w, hip_stream, n_table, out);
+}
+
+extern "C" int skd_state_active_layers(const skd_state *st, int32_t t, int32_t *layers_out) {
+  if (!st || !layers_out) return SKD_ERR_NULL;
+  return state_active_layers(st, t, layers_out);
+}
+
 extern "C" void skd_destroy(skd_state *st) {
   if (!st) return;
   (void)hipStreamSynchronize(st->stream);
@@ -541,8 +580,11 @@ extern "C" int skd_prefill(skd_state *st, const int32_t *tokens, const uint8_t *
   std::fill(st->kv_len.begin(), st->kv_len.end(), 0);
   st->prefilled = false;
   st->steps_done = 0;
-  for (int l = 0; l < c.L; ++l) st->layers_tmp[l] = l;  // the prompt uses every layer
-  for (int i = 0; i < P; ++i) SKDCHECK(run_column(st, i, cols + (size_t)i * B, st->layers_tmp.data(), c.L));
+  for (int i = 0; i < P; ++i) {  // the prompt uses every layer, unless the caller's table decays into it
+    const int n = state_active_layers(st, i, st->layers_tmp.data());
+    if (n < 0) return n;
+    SKDCHECK(run_column(st, i, cols + (size_t)i * B, st->layers_tmp.data(), n));
+  }
   st->prefilled = true;
   if (!c.io_on_device) HIPCHECK(hipStreamSynchronize(st->stream));
   return SKD_OK;
@@ -567,7 +609,7 @@ extern "C" int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_i
     HIPCHECK(hipStreamSynchronize(st->stream));
     tok = st->tok_dev;
   }
-  const int n = skd_active_layers(t, &c, st->layers_tmp.data());
+  const int n = state_active_layers(st, t, st->layers_tmp.data());
   if (n < 0) return n;
   SKDCHECK(run_column(st, t, tok, st->layers_tmp.data(), n));
   st->steps_done += 1;

@@ -21,7 +21,7 @@ BF16, FP32 = 0, 1
 HOST, DEVICE = 0, 1
 W_FP32, W_BF16 = 0, 1
 
-EXPORTS = ["skd_schedule", "skd_active_layers", "skd_create", "skd_prefill", "skd_decode_step",
+EXPORTS = ["skd_schedule", "skd_active_layers", "skd_create", "skd_create_with_schedule", "skd_state_active_layers", "skd_prefill", "skd_decode_step",
            "skd_logits_argmax", "skd_rewind", "skd_profile_enable", "skd_profile_read", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
            "skd_debug_read_hidden", "skd_debug_kv_load", "skd_debug_kv_read", "skd_destroy", "skd_strerror",
            "skd_last_hip_error"]
@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
         l.skd_schedule.argtypes = [C.c_int32] * 6
         l.skd_active_layers.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
         l.skd_create.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.skd_create_with_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.skd_state_active_layers.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         l.skd_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         l.skd_logits_argmax.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -132,7 +134,7 @@ class Decoder:
     """One decoding state (skd_create .. skd_destroy)."""
 
     def __init__(self, cfg: Config, weights: Dict[str, object], location: int = HOST, elem: int = W_FP32,
-                 stream: int = 0):
+                 stream: int = 0, n_table=None):
         """weights: dict with tok_emb, pos_emb, lnf_g, lnf_b, optional lm_head, and per-layer lists named as in
         skd_weights.  Entries are numpy arrays (host), torch tensors, or raw addresses; fp32, or uint16/bfloat16
         bit patterns with elem=W_BF16."""
@@ -159,7 +161,14 @@ class Decoder:
             self._keep.append(tab)
             setattr(w, n, C.cast(tab, _PP))
         h = C.c_void_p()
-        _check(self._lib.skd_create(C.byref(cfg), C.byref(w), C.c_void_p(stream), C.byref(h)), "skd_create")
+        if n_table is None:
+            _check(self._lib.skd_create(C.byref(cfg), C.byref(w), C.c_void_p(stream), C.byref(h)), "skd_create")
+        else:
+            tab = np.ascontiguousarray(n_table, dtype=np.int32)
+            if tab.shape != (cfg.sequence_length,):
+                raise ValueError("n_table needs one entry per position")
+            _check(self._lib.skd_create_with_schedule(C.byref(cfg), C.byref(w), C.c_void_p(stream), tab.ctypes.data,
+                                                      C.byref(h)), "skd_create_with_schedule")
         self._h = h
         self._keep = []   # the library has copied everything
 
@@ -223,6 +232,11 @@ class Decoder:
         n = (C.c_int64 * len(PROF_CLASSES))()
         _check(self._lib.skd_profile_read(self._h, ms, n), "skd_profile_read")
         return {name: {"ms": float(ms[i]), "launches": int(n[i])} for i, name in enumerate(PROF_CLASSES)}
+
+    def active_layers(self, t: int) -> List[int]:
+        out = (C.c_int32 * max(self.cfg.L, 1))()
+        n = _check(self._lib.skd_state_active_layers(self._h, t, out), "skd_state_active_layers")
+        return [int(out[i]) for i in range(n)]
 
     # -- bookkeeping and hooks
     def kv_len(self, layer: int) -> int:

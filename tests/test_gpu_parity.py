@@ -175,3 +175,41 @@ def test_device_io_mode_matches_host_io():
             dec.synchronize()
         np.testing.assert_array_equal(logits.cpu().numpy(), host["logits"])
         np.testing.assert_array_equal(toks.cpu().numpy(), host["logits"].argmax(-1))
+
+
+@pytest.mark.parametrize("dtype,tol", [(skd.FP32, FP32_TOL), (skd.BF16, BF16_TOL)])
+@pytest.mark.parametrize("warm", [0, 1])
+def test_custom_monotone_schedule_table(dtype, tol, warm):
+    # Section 2.3 / Section 5: other decay functions (power law here) and decay that already starts inside the
+    # prompt.  The library takes the per-position layer counts; the oracle is driven with the same layer sets.
+    shape = MID64
+    w = S.make_weights(shape, 11)
+    if dtype == skd.BF16:
+        w = S.weights_to_bf16_values(w)
+    B, P, N = 3, 12, 44
+    table = []
+    for i in range(N):
+        n = shape.L if i < 8 else max(1 + warm, int(round(shape.L * (i - 7) ** -0.55)))
+        table.append(min(n, table[-1]) if table else n)
+    assert table[P - 1] < shape.L and table[-1] == 1 + warm and sorted(table, reverse=True) == table
+    tok = S.make_prompts(B, N, shape.V, 12)
+    cfg = skd.make_config(shape, B, P, N, 1 + warm, shape.L, warm, dtype)
+    ref_dec = O.Decoder(shape, w, B, N)
+    with skd.Decoder(cfg, w, n_table=table) as dec:
+        sets = [dec.active_layers(i) for i in range(N)]
+        for i, A in enumerate(sets):
+            assert len(A) == table[i] and A[:warm] == list(range(warm)) and A[warm:] == list(range(shape.L - (table[i] - warm), shape.L))
+        dec.prefill(tok[:, :P])
+        for i in range(P):
+            ref, _ = ref_dec.column(i, tok[:, i], sets[i], want_logits=(i == P - 1))
+        errs = []
+        for i in range(P - 1, N):
+            if i >= P:
+                dec.decode_step(i, tok[:, i])
+                ref, _ = ref_dec.column(i, tok[:, i], sets[i])
+            _, got = dec.logits_argmax()
+            errs.append(np.abs(got - ref).max() / (ref.max() - ref.min()))
+        assert [dec.kv_len(l) for l in range(shape.L)] == [ref_dec.kv_len(l) for l in range(shape.L)]
+        assert sum(dec.kv_len(l) for l in range(shape.L)) == sum(table)
+    ref_dec.close()
+    assert max(errs) <= tol, errs

@@ -96,3 +96,25 @@ def test_error_codes():
     assert lib.skd_decode_step(None, 0, None) == skd.ERR_NULL
     assert lib.skd_logits_argmax(None, None, None) == skd.ERR_NULL
     assert lib.skd_kv_len(None, 0) == skd.ERR_NULL
+
+
+def test_schedule_table_validation():
+    # caller-supplied layer counts: monotone non-increasing, within [max(1, warmup), L]; checked before any device work
+    lib = skd.lib()
+    h = C.c_void_p()
+    w = skd.Weights()
+    cfg = skd.Config(4, 256, 4, 64, 10, 32, 1, 4, 8, 1, 2, 0, 0, skd.FP32, 0)
+
+    def rc(table, cfg=cfg):
+        import numpy as np
+        t = np.asarray(table, dtype=np.int32)
+        return lib.skd_create_with_schedule(C.byref(cfg), C.byref(w), None, t.ctypes.data, C.byref(h))
+
+    assert rc([4, 4, 4, 4, 3, 3, 2, 1]) == skd.ERR_NULL            # valid table: fails later, on the missing weights
+    assert rc([4, 4, 4, 4, 3, 2, 3, 1]) == skd.ERR_SCHEDULE        # a layer would re-enter
+    assert rc([4, 4, 4, 4, 3, 3, 2, 0]) == skd.ERR_RANGE
+    assert rc([5, 4, 4, 4, 3, 3, 2, 1]) == skd.ERR_RANGE
+    cfgw = skd.Config(4, 256, 4, 64, 10, 32, 1, 4, 8, 2, 3, 2, 0, skd.FP32, 0)
+    assert rc([4, 4, 4, 4, 3, 3, 2, 1], cfgw) == skd.ERR_SHAPE     # falls below the warm-up layers
+    assert lib.skd_create_with_schedule(C.byref(cfg), C.byref(w), None, None, C.byref(h)) == skd.ERR_NULL
+    assert lib.skd_state_active_layers(None, 0, None) == skd.ERR_NULL
