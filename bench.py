@@ -82,7 +82,7 @@ def class_bytes(shape, cls, sum_len):
 
 
 def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, profile, page_tokens=0,
-                   warmup_layers=0):
+                   warmup_layers=0, head="argmax"):
     """Create a state, prefill, warm up, rewind, time `steps` decode steps.  Returns timing dict."""
     N = P + T
     stream = torch.cuda.Stream()
@@ -103,10 +103,15 @@ def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, war
     start = np.zeros(B, dtype=np.int64) if mask is None else (mask == 0).sum(axis=1)
     sum_len = [int((P + k + 1) * B - start.sum()) for k in range(T)]
 
+    uni = torch.rand((T, B), generator=g, dtype=torch.float32).clamp_(0.0, 0.999999).cuda()
+
     def run(k0, k1):
         for k in range(k0, k1):
             dec.decode_step(P + k, tape[k])
-            dec.logits_argmax_device(toks, None)
+            if head == "sample":
+                dec.logits_sample_device(uni[k], 0.3, 0.7, toks, None)
+            else:
+                dec.logits_argmax_device(toks, None)
 
     run(0, min(warmup, T))
     dec.synchronize()
@@ -184,6 +189,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--page-tokens", type=int, default=0, help="KV page size in tokens (0 = library default)")
+    ap.add_argument("--head", choices=["argmax", "sample"], default="argmax",
+                    help="token head after the LM head: greedy argmax (contract) or temperature 0.3 / top-p 0.7 sampling")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run a plain 1 GiB device copy 4 times (reference kernel of known traffic for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -216,7 +223,7 @@ def main():
     if ragged:
         mask = S.make_ragged_mask(B, P, ragged[0], ragged[1], seed=2)
     w = device_weights(shape, 0)
-    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile, args.page_tokens, wl)
+    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile, args.page_tokens, wl, args.head)
     full = None
     if not args.no_full_depth:
         full = run_generation(skd, torch, shape, w, B, P, T, shape.L, shape.L, mask, steps, args.warmup, False, args.page_tokens)
@@ -229,7 +236,7 @@ def main():
         "metric": "generated tokens/sec at OPT-6.7B shape, B=32, skip vs full depth; HBM GB/s",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": skip["ms"] / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic", "head": args.head,
         "config": {"workload": args.workload, "batch": B, "prompt": P, "decode_steps": T,
                    "schedule": f"linear {n_max}->{n_min} of {shape.L} layers" + (f", {wl} warm-up" if wl else ""),
                    "sum_n": int(sum(skip["layers"]))},

@@ -175,6 +175,22 @@ int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_in);
  * processed yet), SKD_ERR_HIP. */
 int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logits_out);
 
+/* Sampling head (the paper's generation setting: temperature 0.3, top-p 0.7,
+ * Section 3.2) in place of the greedy argmax: final LayerNorm + LM head, then
+ * per row, with p_i = exp((z_i - max z) / temperature): the nucleus is the
+ * smallest set of most likely tokens whose mass reaches top_p (tokens tied with
+ * the last admitted one are admitted too), and the token is the first index of
+ * the nucleus, in ascending index order, whose running mass exceeds
+ * u[b] * mass(nucleus).  u [B] are uniform numbers in [0,1) supplied by the
+ * caller (host memory, or device memory with io_on_device = 1): the library
+ * draws no random numbers.  Deterministic for given (state, u).  tokens_out [B]
+ * and logits_out [B][vocab] may be NULL; the tokens are kept for
+ * skd_decode_step(.., NULL).  vocab <= 65536.  Errors: SKD_ERR_NULL,
+ * SKD_ERR_ORDER, SKD_ERR_RANGE (temperature <= 0, top_p outside (0,1], host u
+ * outside [0,1)), SKD_ERR_SHAPE, SKD_ERR_HIP. */
+int skd_logits_sample(skd_state *st, const float *u, float temperature, float top_p, int32_t *tokens_out,
+                      float *logits_out);
+
 /* Move the generation back to position t (P <= t <= current position): the
  * next skd_decode_step must be for column t; cache entries at columns >= t are
  * forgotten (they are overwritten when those columns are processed again).

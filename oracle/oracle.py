@@ -73,6 +73,7 @@ def _lib(real: str) -> C.CDLL:
                                       C.c_void_p]
         lib.ora_op_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]
+        lib.ora_op_sample.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_double, C.c_double, C.c_void_p]
         _LIBS[real] = lib
     return _LIBS[real]
 
@@ -285,3 +286,11 @@ def generate(shape, weights, prompts, P: int, N: int, n_min: int, n_max: int, wa
            "kv_len": [dec.kv_len(l) for l in range(shape.L)]}
     dec.close()
     return res
+
+
+def op_sample(logits, temperature: float, top_p: float, u: float, real: str = "f64"):
+    """Temperature + top-p sampling of one token; returns (token, boundary margin, running-sum margin)."""
+    z = np.ascontiguousarray(logits, dtype=np.float64)
+    m = np.zeros(2, dtype=np.float64)
+    tok = _check(_lib(real).ora_op_sample(z.ctypes.data, z.shape[0], temperature, top_p, u, m.ctypes.data), "op_sample")
+    return tok, float(m[0]), float(m[1])

@@ -561,3 +561,63 @@ done:
   free(qq); free(kk); free(vv); free(oo); free(sc); free(va);
   return rc;
 }
+
+/* ------------------------------------------------------------------ */
+/* Sampling head (the paper's generation setting, Section 3.2)         */
+/* ------------------------------------------------------------------ */
+
+static int cmp_desc(const void *a, const void *b) {
+  const double x = *(const double *)a, y = *(const double *)b;
+  return (x < y) - (x > y);
+}
+
+/* Temperature + nucleus (top-p) sampling of one token from logits[V] with one
+ * uniform number u in [0,1):
+ *   p_i = exp((z_i - max z) / temperature),  Z = sum p_i;
+ *   tau = the largest probability value such that the mass of {p_i >= tau} is at
+ *         least top_p * Z  (the smallest set of most likely tokens reaching
+ *         top_p, tokens tied with the last one included);
+ *   the token is the first index i (ascending) of that set whose running mass
+ *   over the set exceeds u * (mass of the set).
+ * margins[0] = distance of top_p * Z from the two candidate masses around the
+ * boundary (relative to Z), margins[1] = distance of u * mass from the nearest
+ * running-sum boundary (relative to the mass): a checker in lower precision can
+ * only be expected to agree when both are well above its rounding error. */
+int ora_op_sample(const double *logits, int32_t V, double temperature, double top_p, double u, double *margins) {
+  if (!logits) return ORA_ERR_NULL;
+  if (V < 1 || !(temperature > 0) || !(top_p > 0) || top_p > 1 || u < 0 || u >= 1) return ORA_ERR_RANGE;
+  double *p = (double *)malloc(sizeof(double) * V), *srt = (double *)malloc(sizeof(double) * V);
+  if (!p || !srt) { free(p); free(srt); return ORA_ERR_NOMEM; }
+  double mx = logits[0];
+  for (int i = 1; i < V; ++i) if (logits[i] > mx) mx = logits[i];
+  double Z = 0;
+  for (int i = 0; i < V; ++i) { p[i] = exp((logits[i] - mx) / temperature); Z += p[i]; srt[i] = p[i]; }
+  qsort(srt, V, sizeof(double), cmp_desc);
+  const double target = top_p * Z;
+  double cum = 0, tau = srt[V - 1], before = 0;
+  for (int i = 0; i < V; ++i) {
+    cum += srt[i];
+    if (cum >= target) { tau = srt[i]; break; }
+  }
+  double mass = 0, above = 0;
+  for (int i = 0; i < V; ++i) { if (p[i] >= tau) mass += p[i]; if (p[i] > tau) above += p[i]; }
+  before = above; /* mass of the strictly larger values: must be below the target */
+  const double goal = u * mass;
+  double run = 0, m1 = 1e300;
+  int tok = -1;
+  for (int i = 0; i < V; ++i) {
+    if (p[i] < tau) continue;
+    if (tok < 0 && run + p[i] > goal) tok = i;
+    run += p[i];
+    if (fabs(run - goal) < m1) m1 = fabs(run - goal);
+  }
+  if (tok < 0)
+    for (int i = V - 1; i >= 0; --i) if (p[i] >= tau) { tok = i; break; }
+  if (margins) {
+    double a = fabs(mass - target), b = fabs(target - before);
+    margins[0] = top_p >= 1.0 ? 1.0 : (a < b ? a : b) / Z; /* top_p = 1: everything is in, nothing to decide */
+    margins[1] = m1 / mass;
+  }
+  free(p); free(srt);
+  return tok;
+}

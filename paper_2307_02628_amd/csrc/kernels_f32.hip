@@ -135,6 +135,94 @@ __global__ void k_f32_argmax(const float *logits, int32_t *tokens, int V) {
   if (threadIdx.x == 0) tokens[blockIdx.x] = si[0];
 }
 
+// ------------------------------------------------------------------ sampling head (both paths; fp32 logits)
+// Temperature + nucleus (top-p) sampling, one 1024-thread workgroup per row.
+// Thread t keeps tokens [t*C, (t+1)*C) in registers, C = ceil(V / 1024) <= 64.
+//   p_i = exp((z_i - max z) / T);  nucleus = {p_i >= tau}, tau = the largest value whose upper set has mass
+//   >= top_p * sum p  (found bit by bit on the float bit pattern, 31 block sums; tokens tied with tau are in);
+//   token = first index of the nucleus whose running mass (ascending index) exceeds u * mass(nucleus).
+// Every sum is taken in a fixed order, so a given (logits, u) always yields the same token.
+constexpr int SAMPLE_C = 64;
+
+__global__ __launch_bounds__(1024) void k_sample_top_p(const float *logits, int V, float inv_temp, float top_p,
+                                                       const float *u, int32_t *tokens) {
+  __shared__ float sh[16];
+  __shared__ int first_hit, last_in;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = (V + 1023) / 1024, base = tid * C;
+  const float *z = logits + (long)b * V;
+  float p[SAMPLE_C];
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int j = 0; j < SAMPLE_C; ++j) {
+    p[j] = (j < C && base + j < V) ? z[base + j] * inv_temp : -3.0e38f;
+    mx = fmaxf(mx, p[j]);
+  }
+  mx = wave_max(mx);
+  if (lane == 0) sh[wave] = mx;
+  __syncthreads();
+  mx = sh[0];
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, sh[w]);
+  float loc = 0;
+#pragma unroll
+  for (int j = 0; j < SAMPLE_C; ++j) {
+    p[j] = (j < C && base + j < V) ? expf(p[j] - mx) : 0.f;
+    loc += p[j];
+  }
+  const float target = top_p * block_sum(loc, sh);
+  unsigned T = 0;
+  for (int bit = 30; bit >= 0; --bit) {
+    const unsigned cand = T | (1u << bit);
+    float m = 0;
+#pragma unroll
+    for (int j = 0; j < SAMPLE_C; ++j) m += (__float_as_uint(p[j]) >= cand) ? p[j] : 0.f;
+    if (block_sum(m, sh) >= target) T = cand;  // uniform decision: every thread sees the same sum
+  }
+  loc = 0;
+#pragma unroll
+  for (int j = 0; j < SAMPLE_C; ++j) {
+    if (__float_as_uint(p[j]) < T || !(j < C && base + j < V)) p[j] = 0.f;  // outside the nucleus
+    loc += p[j];
+  }
+  // exclusive prefix of the per-thread masses in index order
+  float inc = loc;
+  for (int off = 1; off < 64; off <<= 1) {
+    const float t = __shfl_up(inc, off);
+    if (lane >= off) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) sh[wave] = inc;
+  if (tid == 0) { first_hit = 0x7fffffff; last_in = -1; }
+  __syncthreads();
+  float excl = inc - loc, mass = 0;
+  for (int w = 0; w < 16; ++w) {
+    if (w < wave) excl += sh[w];
+    mass += sh[w];
+  }
+  const float goal = u[b] * mass;
+  float run = excl;
+  int hit = 0x7fffffff, last = -1;
+#pragma unroll
+  for (int j = 0; j < SAMPLE_C; ++j) {
+    if (p[j] > 0.f) {
+      if (hit == 0x7fffffff && run + p[j] > goal) hit = base + j;
+      run += p[j];
+      last = base + j;
+    }
+  }
+  if (hit != 0x7fffffff) atomicMin(&first_hit, hit);
+  if (last >= 0) atomicMax(&last_in, last);
+  __syncthreads();
+  if (tid == 0) tokens[b] = first_hit != 0x7fffffff ? first_hit : last_in;  // rounding at the very end: last member
+}
+
+int sample_top_p(hipStream_t s, const float *logits, int B, int V, float temperature, float top_p, const float *u,
+                 int32_t *tokens) {
+  if (V > 1024 * SAMPLE_C) return -1;
+  hipLaunchKernelGGL(k_sample_top_p, dim3(B), dim3(1024), 0, s, logits, V, 1.0f / temperature, top_p, u, tokens);
+  return 0;
+}
+
 void f32_embed(hipStream_t s, float *x, const float *tok_emb, const float *pos_emb, const int32_t *tokens,
                const int32_t *start, int t, int B, int d, int V) {
   hipLaunchKernelGGL(k_f32_embed, dim3(B), dim3(256), 0, s, x, tok_emb, pos_emb, tokens, start, t, d, V);

@@ -70,6 +70,7 @@ struct skd_state {
   int32_t *prompt_dev = nullptr;   // [P][B]
   int32_t *start_dev = nullptr;    // [B] first real column
   int32_t *argmax_dev = nullptr;   // [B]
+  float *u_dev = nullptr;          // [B] uniform numbers of the sampling head
   float *x = nullptr;              // residual stream fp32 [B_pad][d]
   void *a = nullptr;               // LayerNorm output
   void *q = nullptr;               // bf16: q [B_pad][d]; fp32: qkv [B][3d]
@@ -472,7 +473,7 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   // ---- workspaces
   const int Bp = st->B_pad;
   auto A = [&](auto **p, size_t n) { if (rc == SKD_OK) rc = dev_alloc(st, p, n); };
-  A(&st->tok_dev, B); A(&st->prompt_dev, (size_t)c.prompt_size * B); A(&st->start_dev, B); A(&st->argmax_dev, B);
+  A(&st->tok_dev, B); A(&st->prompt_dev, (size_t)c.prompt_size * B); A(&st->start_dev, B); A(&st->argmax_dev, B); A(&st->u_dev, B);
   A(&st->x, (size_t)Bp * d);
   if (st->bf16) {
     st->p_qkv = plan_direct(3 * d, Bp);
@@ -617,14 +618,11 @@ extern "C" int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_i
   return SKD_OK;
 }
 
-extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logits_out) {
-  if (!st) return SKD_ERR_NULL;
-  if (!st->have_hidden) return SKD_ERR_ORDER;
+// Final LayerNorm + LM head (+ greedy argmax into argmax_dev).  logits_target: device buffer [B][V] or null.
+static int head_logits(skd_state *st, float *logits_target) {
   const skd_config &c = st->cfg;
   const int B = c.batch, d = c.d_model, V = c.vocab;
   hipStream_t s = st->stream;
-  float *logits_target = nullptr;  // where the kernels write logits, if anywhere
-  if (logits_out) logits_target = c.io_on_device ? logits_out : st->logits_dev;
   if (!st->bf16) {
     float *lg = logits_target ? logits_target : st->logits_dev;
     { ProfScope ps_(st, SKD_PROF_OTHER); f32_layernorm(s, st->x, st->lnf_g, st->lnf_b, (float *)st->a, B, d); }
@@ -640,7 +638,53 @@ extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logi
     { ProfScope ps_(st, SKD_PROF_ARGMAX); bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B); }
   }
   HIPCHECK(hipGetLastError());
+  return SKD_OK;
+}
+
+extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logits_out) {
+  if (!st) return SKD_ERR_NULL;
+  if (!st->have_hidden) return SKD_ERR_ORDER;
+  const skd_config &c = st->cfg;
+  const int B = c.batch, V = c.vocab;
+  hipStream_t s = st->stream;
+  float *logits_target = nullptr;  // where the kernels write logits, if anywhere
+  if (logits_out) logits_target = c.io_on_device ? logits_out : st->logits_dev;
+  SKDCHECK(head_logits(st, logits_target));
   st->have_argmax = true;
+  if (c.io_on_device) {
+    if (tokens_out)
+      HIPCHECK(hipMemcpyAsync(tokens_out, st->argmax_dev, B * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    return SKD_OK;
+  }
+  if (tokens_out) HIPCHECK(hipMemcpyAsync(tokens_out, st->argmax_dev, B * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (logits_out)
+    HIPCHECK(hipMemcpyAsync(logits_out, st->logits_dev, (size_t)B * V * sizeof(float), hipMemcpyDeviceToHost, s));
+  HIPCHECK(hipStreamSynchronize(s));
+  return SKD_OK;
+}
+
+extern "C" int skd_logits_sample(skd_state *st, const float *u, float temperature, float top_p, int32_t *tokens_out,
+                                 float *logits_out) {
+  if (!st || !u) return SKD_ERR_NULL;
+  if (!st->have_hidden) return SKD_ERR_ORDER;
+  if (!(temperature > 0.f) || !(top_p > 0.f) || top_p > 1.f) return SKD_ERR_RANGE;
+  const skd_config &c = st->cfg;
+  const int B = c.batch, V = c.vocab;
+  if (V > 65536) return SKD_ERR_SHAPE;
+  hipStream_t s = st->stream;
+  const float *u_dev = u;
+  if (!c.io_on_device) {
+    for (int b = 0; b < B; ++b)
+      if (!(u[b] >= 0.f) || u[b] >= 1.f) return SKD_ERR_RANGE;
+    HIPCHECK(hipMemcpyAsync(st->u_dev, u, B * sizeof(float), hipMemcpyHostToDevice, s));
+    HIPCHECK(hipStreamSynchronize(s));
+    u_dev = st->u_dev;
+  }
+  float *lg = (logits_out && c.io_on_device) ? logits_out : st->logits_dev;
+  SKDCHECK(head_logits(st, lg));
+  { ProfScope ps_(st, SKD_PROF_ARGMAX); if (sample_top_p(s, lg, B, V, temperature, top_p, u_dev, st->argmax_dev) < 0) return SKD_ERR_SHAPE; }
+  HIPCHECK(hipGetLastError());
+  st->have_argmax = true;  // skd_decode_step(.., NULL) continues from the sampled tokens
   if (c.io_on_device) {
     if (tokens_out)
       HIPCHECK(hipMemcpyAsync(tokens_out, st->argmax_dev, B * sizeof(int32_t), hipMemcpyDeviceToDevice, s));

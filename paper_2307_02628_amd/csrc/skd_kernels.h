@@ -29,6 +29,9 @@ void f32_kv_write(hipStream_t s, const float *qkv, float *pool, const int32_t *b
 void f32_attention(hipStream_t s, const float *qkv, const float *pool, const int32_t *bt_layer, const int32_t *start,
                    int t, float *o, float *scores, int score_stride, int B, KvGeom g);
 void f32_argmax(hipStream_t s, const float *logits, int32_t *tokens, int B, int V);
+// temperature + top-p sampling from fp32 logits [B][V] with one uniform number per row; -1 if V > 65536
+int sample_top_p(hipStream_t s, const float *logits, int B, int V, float temperature, float top_p, const float *u,
+                 int32_t *tokens);
 
 // ---------------------------------------------------------------- bf16 production path
 // "Fragment-major" layout of a [rows][K] bf16 matrix (weights: rows = output

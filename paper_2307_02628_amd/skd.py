@@ -22,7 +22,7 @@ HOST, DEVICE = 0, 1
 W_FP32, W_BF16 = 0, 1
 
 EXPORTS = ["skd_schedule", "skd_active_layers", "skd_create", "skd_create_with_schedule", "skd_state_active_layers", "skd_prefill", "skd_decode_step",
-           "skd_logits_argmax", "skd_rewind", "skd_profile_enable", "skd_profile_read", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
+           "skd_logits_argmax", "skd_logits_sample", "skd_rewind", "skd_profile_enable", "skd_profile_read", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
            "skd_debug_read_hidden", "skd_debug_kv_load", "skd_debug_kv_read", "skd_destroy", "skd_strerror",
            "skd_last_hip_error"]
 
@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         l.skd_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         l.skd_logits_argmax.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        l.skd_logits_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         l.skd_rewind.argtypes = [C.c_void_p, C.c_int32]
         l.skd_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         l.skd_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -216,6 +217,25 @@ class Decoder:
         lg = np.zeros((self.cfg.batch, self.cfg.vocab), dtype=np.float32) if want_logits else None
         _check(self._lib.skd_logits_argmax(self._h, tok.ctypes.data, _ptr_of(lg)), "skd_logits_argmax")
         return tok, lg
+
+    def logits_sample_rc(self, u, temperature: float, top_p: float, want_logits: bool = True):
+        """Host-I/O form of skd_logits_sample: returns (rc, tokens[B], logits[B,V] or None)."""
+        assert not self.cfg.io_on_device
+        uu = np.ascontiguousarray(u, dtype=np.float32)
+        tok = np.zeros(self.cfg.batch, dtype=np.int32)
+        lg = np.zeros((self.cfg.batch, self.cfg.vocab), dtype=np.float32) if want_logits else None
+        rc = self._lib.skd_logits_sample(self._h, uu.ctypes.data, temperature, top_p, tok.ctypes.data, _ptr_of(lg))
+        return rc, tok, lg
+
+    def logits_sample(self, u, temperature: float, top_p: float, want_logits: bool = True):
+        rc, tok, lg = self.logits_sample_rc(u, temperature, top_p, want_logits)
+        _check(rc, "skd_logits_sample")
+        return tok, lg
+
+    def logits_sample_device(self, u, temperature: float, top_p: float, tokens_out=None, logits_out=None):
+        """Device-I/O form: u, tokens_out, logits_out are device pointers / torch tensors; asynchronous."""
+        _check(self._lib.skd_logits_sample(self._h, _ptr_of(u), temperature, top_p, _ptr_of(tokens_out),
+                                           _ptr_of(logits_out)), "skd_logits_sample")
 
     def logits_argmax_device(self, tokens_out=None, logits_out=None):
         """Device-I/O form: pointers / torch tensors on the device; asynchronous."""

@@ -213,3 +213,82 @@ def test_custom_monotone_schedule_table(dtype, tol, warm):
         assert sum(dec.kv_len(l) for l in range(shape.L)) == sum(table)
     ref_dec.close()
     assert max(errs) <= tol, errs
+
+
+@pytest.mark.parametrize("dtype", [skd.FP32, skd.BF16])
+def test_sampling_head_matches_oracle(dtype):
+    # Temperature / top-p sampling (Section 3.2).  The HIP sampler and the oracle's sampler are given the same
+    # logits (the HIP path's own, read back) and the same uniform numbers; tokens must agree wherever the
+    # oracle's decision margins are above fp32 rounding.  Then greedy-free generation continues from the samples.
+    shape = S.TINY
+    w = S.make_weights(shape, 0)
+    if dtype == skd.BF16:
+        w = S.weights_to_bf16_values(w)
+    B, P, N = 2, 16, 32
+    pr = S.make_prompts(B, P, shape.V, 1)
+    cfg = skd.make_config(shape, B, P, N, 2, 4, dtype=dtype)
+    rng = np.random.default_rng(5)
+    checked = 0
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        for temperature, top_p in ((0.3, 0.7), (1.0, 0.9), (2.0, 1.0), (0.05, 0.5)):
+            for _ in range(25):
+                u = rng.random(B).astype(np.float32)
+                tok, lg = dec.logits_sample(u, temperature, top_p)
+                _, lg2 = dec.logits_argmax()
+                np.testing.assert_array_equal(lg, lg2)                       # same logits as the argmax head
+                for b in range(B):
+                    ref, m_set, m_run = O.op_sample(lg[b], temperature, top_p, float(u[b]))
+                    if m_set > 1e-5 and m_run > 1e-5:
+                        assert tok[b] == ref, (temperature, top_p, u[b], m_set, m_run)
+                        checked += 1
+        assert checked > 180
+        # invalid arguments
+        assert dec.logits_sample_rc(np.array([0.5, 1.0], np.float32), 0.3, 0.7)[0] == skd.ERR_RANGE
+        assert dec.logits_sample_rc(np.array([0.5, 0.5], np.float32), 0.0, 0.7)[0] == skd.ERR_RANGE
+        assert dec.logits_sample_rc(np.array([0.5, 0.5], np.float32), 0.3, 1.5)[0] == skd.ERR_RANGE
+        # free-running from sampled tokens: the next column's input is the sample
+        u = rng.random(B).astype(np.float32)
+        tok, _ = dec.logits_sample(u, 0.3, 0.7)
+        dec.decode_step(P, None)
+        _, lg_free = dec.logits_argmax()
+        dec.rewind(P)
+        dec.decode_step(P, tok)
+        _, lg_forced = dec.logits_argmax()
+        np.testing.assert_array_equal(lg_free, lg_forced)
+
+
+def test_sampling_head_full_vocab_distribution():
+    # vocabulary 50272 (49.1 tokens per thread, ragged tail): frequencies over a grid of uniform numbers follow the
+    # renormalised nucleus probabilities, and every sample lies in the nucleus
+    shape = S.ModelShape(L=1, d=128, H=2, f=128, V=50272, max_pos=8)
+    w = S.make_weights(shape, 3)
+    g = np.random.Generator(np.random.Philox(key=[3, 99]))
+    # an untied LM head with a wider spread, so that the nucleus at temperature 0.3 is a few hundred tokens
+    w["lm_head"] = (g.standard_normal(size=(shape.V, shape.d), dtype=np.float32) * np.float32(0.09))
+    w = S.weights_to_bf16_values(w)
+    B, P, N = 64, 2, 4
+    pr = np.tile(S.make_prompts(1, P, shape.V, 4), (B, 1))   # identical rows: identical logits in every row
+    cfg = skd.make_config(shape, B, P, N, 1, 1, dtype=skd.BF16)
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        toks = []
+        for r in range(16):
+            u = ((np.arange(B) + r * B + 0.5) / (16 * B)).astype(np.float32)
+            tok, lg = dec.logits_sample(u, 0.3, 0.7, want_logits=(r == 0))
+            if r == 0:
+                logits = lg[0].astype(np.float64)
+                assert np.abs(lg - lg[0]).max() == 0
+            toks.append(tok)
+    toks = np.concatenate(toks)
+    p = np.exp((logits - logits.max()) / 0.3)
+    p /= p.sum()
+    order = np.argsort(-p, kind="stable")
+    k = int(np.searchsorted(np.cumsum(p[order]), 0.7, side="left")) + 1
+    nucleus = order[:k]
+    assert 20 < k < 20000
+    assert set(toks.tolist()) <= set(nucleus.tolist())
+    mass = p[nucleus].sum()
+    top = nucleus[:5]
+    for i in top:
+        assert abs((toks == i).mean() - p[i] / mass) < 2.5 / len(toks) + 1e-3

@@ -252,3 +252,42 @@ def test_ops_against_library():
         s[valid == 0] = -np.inf
         p = torch.softmax(torch.from_numpy(s), 0).numpy()
         np.testing.assert_allclose(out[sl], p @ V[:, sl], atol=1e-12)
+
+
+def test_sampling_head_pins():
+    # Section 3.2 generation setting (temperature, top-p): hand-computed cases, limits and the library softmax.
+    lg = np.log(np.array([0.5, 0.3, 0.2]))
+    # nucleus for top_p 0.7 is {0, 1} (0.5 alone is short of 0.7); running sums 0.5, 0.8 over a mass of 0.8
+    assert O.op_sample(lg, 1.0, 0.7, 0.50)[0] == 0          # 0.5 * 0.8 = 0.40 < 0.5
+    assert O.op_sample(lg, 1.0, 0.7, 0.63)[0] == 1          # 0.504 > 0.5
+    assert O.op_sample(lg, 1.0, 0.7, 0.999)[0] == 1         # token 2 is outside the nucleus
+    assert O.op_sample(lg, 1.0, 0.5, 0.999)[0] == 0         # 0.5 reaches top_p = 0.5 on its own
+    assert O.op_sample(lg, 1.0, 1.0, 0.999)[0] == 2         # everything is in
+    assert O.op_sample(lg, 0.01, 1.0, 0.999)[0] == 0        # temperature -> 0 is the argmax
+    # ties with the last admitted value are admitted too: [0.4, 0.3, 0.3], top_p 0.6 -> all three
+    tie = np.log(np.array([0.4, 0.3, 0.3]))
+    assert O.op_sample(tie, 1.0, 0.6, 0.95)[0] == 2
+    # top_p = 1: plain inverse-CDF sampling of softmax(z / T), against the library softmax
+    rng = np.random.default_rng(3)
+    z = rng.standard_normal(500) * 2
+    for T in (0.3, 1.0, 1.7):
+        p = torch.softmax(torch.from_numpy(z / T), 0).numpy()
+        cdf = np.cumsum(p)
+        for u in rng.random(50):
+            tok, _, m = O.op_sample(z, T, 1.0, float(u))
+            if m > 1e-9:
+                assert tok == int(np.searchsorted(cdf, u, side="right"))
+    # with top_p < 1 the sample always lies in the smallest top set reaching top_p, and its frequency follows the
+    # renormalised probabilities
+    z = rng.standard_normal(40)
+    T, tp = 0.5, 0.7
+    p = torch.softmax(torch.from_numpy(z / T), 0).numpy()
+    order = np.argsort(-p)
+    k = int(np.searchsorted(np.cumsum(p[order]), tp, side="left")) + 1
+    nucleus = set(order[:k].tolist())
+    us = (np.arange(20000) + 0.5) / 20000
+    toks = np.array([O.op_sample(z, T, tp, float(u))[0] for u in us])
+    assert set(toks.tolist()) == nucleus
+    mass = sum(p[i] for i in nucleus)
+    for i in nucleus:
+        assert abs((toks == i).mean() - p[i] / mass) < 2e-4
