@@ -40,6 +40,8 @@ WORKLOADS = {
     # two layers of the 6.7B shape with the primary workload's batch and lengths: same per-launch kernel shapes,
     # short enough for counter collection
     "opt6.7b-2layers_b32_p512_t256_2to1": (S.ModelShape(2, 4096, 32, 16384, 50272, 3072), 32, 512, 256, 1, 2, None),
+    "opt6.7b-2layers_b128_p64-512_t128_2to1": (S.ModelShape(2, 4096, 32, 16384, 50272, 3072), 128, 512, 128, 1, 2,
+                                                (64, 512)),
 }
 for _x, (_w, _lo, _hi) in TABLE2["opt6.7b"].items():   # the paper's presets at the primary workload's batch and lengths
     WORKLOADS[f"opt6.7b_b32_p512_t256_table2-{_x}x"] = (S.OPT_6_7B, 32, 512, 256, _lo, _hi, None, _w)
