@@ -291,3 +291,30 @@ def test_sampling_head_pins():
     mass = sum(p[i] for i in nucleus)
     for i in nucleus:
         assert abs((toks == i).mean() - p[i] / mass) < 2e-4
+
+
+def test_argmax_lowest_index_on_ties():
+    # greedy head: the lowest index attaining the maximum.  With identical vocabulary rows every logit ties.
+    w = S.make_weights(SMALL, seed=31)
+    w["tok_emb"] = np.tile(w["tok_emb"][5:6], (SMALL.V, 1))
+    tok = S.make_prompts(2, 3, SMALL.V, 32)
+    dec = O.Decoder(SMALL, w, 2, 3)
+    for i in range(3):
+        lg, am = dec.column(i, tok[:, i], list(range(SMALL.L)))
+        assert (lg == lg[:, :1]).all()
+        assert am.tolist() == [0, 0]
+    dec.close()
+    # and a tie between two entries only, one of them the maximum
+    w = S.make_weights(SMALL, seed=33)
+    dec = O.Decoder(SMALL, w, 1, 1)
+    lg, am = dec.column(0, [4], list(range(SMALL.L)))
+    dec.close()
+    top = int(lg[0].argmax())
+    other = (top + 11) % SMALL.V
+    w["tok_emb"][other] = w["tok_emb"][top]
+    dec = O.Decoder(SMALL, w, 1, 1)
+    lg2, am2 = dec.column(0, [4], list(range(SMALL.L)))
+    dec.close()
+    if 4 not in (top, other):                    # the input embedding itself was not touched
+        assert lg2[0, other] == lg2[0, top] == lg2[0].max()
+        assert am2[0] == min(top, other)
