@@ -292,3 +292,36 @@ def test_sampling_head_full_vocab_distribution():
     top = nucleus[:5]
     for i in top:
         assert abs((toks == i).mean() - p[i] / mass) < 2.5 / len(toks) + 1e-3
+
+
+@pytest.mark.parametrize("dtype,tol", [(skd.FP32, FP32_TOL), (skd.BF16, BF16_TOL)])
+def test_minimal_sizes(dtype, tol):
+    # one row, one prompt token, two decode steps; and a prompt that ends exactly on a page boundary
+    w = S.make_weights(MID64, 13)
+    if dtype == skd.BF16:
+        w = S.weights_to_bf16_values(w)
+    compare(MID64, w, S.make_prompts(1, 1, MID64.V, 14), 1, 3, 1, 5, tol, dtype=dtype)
+    compare(MID64, w, S.make_prompts(2, 32, MID64.V, 15), 32, 66, 2, 5, tol, dtype=dtype, page_tokens=32)
+
+
+def test_rewind_regenerates_identically():
+    w = bf16_weights(S.TINY, 0)
+    pr = S.make_prompts(2, 16, S.TINY.V, 1)
+    tape = S.make_token_tape(2, 16, S.TINY.V, 17)
+    cfg = skd.make_config(S.TINY, 2, 16, 32, 2, 4)
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        first = []
+        for k in range(10):
+            dec.decode_step(16 + k, tape[k])
+            first.append(dec.logits_argmax()[1])
+        lens = [dec.kv_len(l) for l in range(4)]
+        assert dec._lib.skd_rewind(dec._h, 27) == skd.ERR_RANGE      # beyond the current position
+        assert dec._lib.skd_rewind(dec._h, 15) == skd.ERR_RANGE      # inside the prompt
+        dec.rewind(20)
+        assert [dec.kv_len(l) for l in range(4)] == [min(x, 20) for x in lens]
+        assert dec._lib.skd_logits_argmax(dec._h, None, None) == skd.ERR_ORDER   # no hidden state after a rewind
+        for k in range(4, 10):
+            dec.decode_step(16 + k, tape[k])
+            np.testing.assert_array_equal(dec.logits_argmax()[1], first[k])
+        assert [dec.kv_len(l) for l in range(4)] == lens
