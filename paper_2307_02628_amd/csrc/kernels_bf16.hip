@@ -118,6 +118,37 @@ constexpr int gemm_stage_rows(int waves, int R, int MB) {
   return fit >= R ? R : (fit > 0 ? fit : 1);
 }
 
+template <>
+__device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, int n0, floatx4 v, int) {
+  if (n0 >= a.N || row >= a.rows) return;
+  const int b = row / a.P_pad, pos = row - b * a.P_pad;
+  if (b >= a.B || pos >= a.P) return;  // padding rows (of the 16-position tiles, of the last 128-row chunk)
+  for (int i = 0; i < 4; ++i) v[i] += a.bias[n0 + i];
+  const int which = n0 / a.d, within = n0 - which * a.d;
+  const uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+  if (which == 0) {
+    *(uint2 *)&a.q_out[d_frag_index(row, within, a.d)] = pk;
+    return;
+  }
+  const int h = within / a.kv.dh, e = within - h * a.kv.dh;
+  const int page = a.bt_layer[(long)b * a.kv.max_pages + pos / a.kv.page_tokens];
+  bf16_t *pg = a.kv_pool + (long)page * a.kv.page_elems;
+  const int tt = pos % a.kv.page_tokens;
+  if (which == 1) {
+    *(uint2 *)&pg[kv_k_off(h, tt, e, a.kv)] = pk;
+  } else {
+    for (int i = 0; i < 4; ++i) pg[kv_v_off(h, tt, e + i, a.kv)] = (bf16_t)f2bf(v[i]);
+  }
+}
+
+template <>
+__device__ inline void gemm_epilogue<EPI_RESID>(const GemmArgs &a, int row, int n0, floatx4 v, int) {
+  if (n0 + 3 >= a.N || row >= a.rows) return;
+  floatx4 *xp = (floatx4 *)&a.x[(long)row * a.N + n0];
+  const floatx4 bias = *(const floatx4 *)&a.bias[n0];
+  *xp = *xp + (v + bias);
+}
+
 template <int MB, int R, int EPI, int U, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
   constexpr int RM = R * MB;
@@ -130,7 +161,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
   const int kw0 = (int)((long)Kf * blockIdx.y / a.split), kw1 = (int)((long)Kf * (blockIdx.y + 1) / a.split);
   const int nbuf = (kw1 - kw0) / U;  // the launcher picks U so that this is exact
   const bf16x8 *Wb = (const bf16x8 *)a.W + ((long)blockIdx.x * R * Kf + kw0) * 64 + lane;
-  const bf16x8 *Ab = (const bf16x8 *)a.A + (long)kw0 * 64 + lane;
+  const int row0 = blockIdx.z * (MB * 16);  // chunk of activation rows (0 when decoding)
+  const bf16x8 *Ab = (const bf16x8 *)a.A + ((long)blockIdx.z * MB * Kf + kw0) * 64 + lane;
 
   floatx4 acc[R][MB];
 #pragma unroll
@@ -192,7 +224,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
         if (r < R) {
           floatx4 v = red[p * 64 + lane];
           for (int w = 1; w < WAVES; ++w) v += red[(w * (RS * MB) + p) * 64 + lane];
-          gemm_epilogue<EPI>(a, m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
+          gemm_epilogue<EPI>(a, row0 + m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
         }
       }
     }
@@ -261,6 +293,12 @@ static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid
     case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL, U, WAVES>), grid, blk, lds, s, a); break;
     case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV, U, WAVES>), grid, blk, lds, s, a); break;
     case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU, U, WAVES>), grid, blk, lds, s, a); break;
+    case EPI_QKV_ROWS:
+      if constexpr (MB == 8) hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV_ROWS, U, WAVES>), grid, blk, lds, s, a);
+      break;
+    case EPI_RESID:
+      if constexpr (MB == 8) hipLaunchKernelGGL((k_gemm<MB, R, EPI_RESID, U, WAVES>), grid, blk, lds, s, a);
+      break;
     default:
       if constexpr (gemm_stage_rows(WAVES, R, MB) == R)
         hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a);
@@ -303,7 +341,10 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
   if (Kf % split) return -1;            // equal K ranges per workgroup
   while (U > 1 && (Kf / split) % U) U >>= 1;  // whole buffers only
   const int groups = bf16_gemm_groups(a.N, R);
-  const dim3 grid(groups, split);
+  const bool by_rows = epi == EPI_QKV_ROWS || epi == EPI_RESID || (epi == EPI_RELU && a.rows > 0);
+  if ((epi == EPI_QKV_ROWS || epi == EPI_RESID) && (MB != 8 || a.rows <= 0)) return -1;
+  if (by_rows && (a.rows % a.B_pad || split != 1)) return -1;
+  const dim3 grid(groups, split, by_rows ? a.rows / a.B_pad : 1);
   switch (MB) {
     case 1: launch_gemm_r<1>(s, a, epi, R, U, waves, grid); break;
     case 2: launch_gemm_r<2>(s, a, epi, R, U, waves, grid); break;
@@ -553,6 +594,181 @@ void bf16_attention(hipStream_t s, const AttnArgs &a) {
     hipLaunchKernelGGL(k_attention<128>, grid, dim3(256), 0, s, a);
     if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<128>, dim3(a.B * a.kv.H), dim3(128), 0, s, a);
   }
+}
+
+// ------------------------------------------------------------------ causal attention over a whole prompt
+// Same structure as k_attention, but the 16 MFMA columns now carry 16 different
+// queries (consecutive positions of one sequence) instead of one replicated
+// query: one workgroup per (row b, head h, 16-position tile).  Softmax state is
+// per column; key blocks are dealt round-robin to the 4 waves and merged at the
+// end.  Keys: start[b] .. own position (causal).
+template <int DH>
+__global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
+  constexpr int QC = DH / 32, VM = DH / 16;
+  __shared__ float sm_m[4][16], sm_l[4][16];
+  __shared__ float sm_o[4][DH][17];  // padded: columns of one dh row fall into different banks
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4, col = lane & 15;
+  const int H = a.kv.H, b = blockIdx.x / H, h = blockIdx.x % H, d = H * DH;
+  const int p0 = blockIdx.y * 16;                 // first position of the tile
+  const long row0 = (long)b * a.P_pad + p0;       // multiple of 16
+  const int j0 = a.start[b];
+  const int my_pos = p0 + col;                    // this column's query position
+  const int last = min(p0 + 15, a.P - 1);         // last real position of the tile
+  const int blk_lo = j0 >> 5, blk_hi = (last >> 5) + 1;
+  const int bpp = a.kv.page_tokens >> 5;
+  const int32_t *bt_row = a.bt_layer + (long)b * a.kv.max_pages;
+  const float scale = 1.0f / sqrtf((float)DH);
+
+  bf16x8 qf[QC];
+#pragma unroll
+  for (int c = 0; c < QC; ++c)
+    qf[c] = ((const bf16x8 *)a.q)[((row0 >> 4) * (d >> 5) + ((h * DH) >> 5) + c) * 64 + lane];
+
+  floatx4 O[VM];
+#pragma unroll
+  for (int m = 0; m < VM; ++m) O[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -1.0e30f, l_run = 0.f;
+
+  for (int blk = blk_lo + wave; blk < blk_hi; blk += 4) {
+    const int page = bt_row[blk / bpp];
+    const bf16x8 *kp = (const bf16x8 *)(a.pool + (long)page * a.kv.page_elems + (long)h * (a.kv.page_tokens * DH * 2) +
+                                        (long)(blk % bpp) * (64 * DH)) + lane;
+    bf16x8 kf[2][QC], vf[VM];
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+      for (int c = 0; c < QC; ++c) kf[tl][c] = kp[(tl * QC + c) * 64];
+#pragma unroll
+    for (int m = 0; m < VM; ++m) vf[m] = kp[4 * DH + m * 64];
+    floatx4 S[2];
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+      S[tl] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < QC; ++c) S[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tl][c], qf[c], S[tl], 0, 0, 0);
+    }
+    float sv[8];
+    bool ok[8];
+    float bm = -1.0e30f;
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = blk * 32 + 16 * tl + 4 * grp + i;
+        ok[tl * 4 + i] = (key >= j0) && (key <= my_pos);
+        sv[tl * 4 + i] = S[tl][i] * scale;
+        if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
+      }
+    bm = fmaxf(bm, __shfl_xor(bm, 16));  // lanes 16 and 32 apart hold the same query column
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    const float m_new = fmaxf(m_run, bm);
+    const float alpha = __expf(m_run - m_new);
+    float ps = 0.f;
+    uint32_t pk[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float p_lo = ok[2 * j] ? __expf(sv[2 * j] - m_new) : 0.f;
+      const float p_hi = ok[2 * j + 1] ? __expf(sv[2 * j + 1] - m_new) : 0.f;
+      pk[j] = pack2(p_lo, p_hi);
+      ps += bf2f(pk[j] & 0xffffu) + bf2f(pk[j] >> 16);
+    }
+    l_run = l_run * alpha + ps;
+    m_run = m_new;
+    const uint32x4 pku = uint32x4{pk[0], pk[1], pk[2], pk[3]};
+    const bf16x8 pv = __builtin_bit_cast(bf16x8, pku);
+#pragma unroll
+    for (int m = 0; m < VM; ++m) {
+      O[m] *= alpha;
+      O[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[m], pv, O[m], 0, 0, 0);
+    }
+  }
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (grp == 0) { sm_m[wave][col] = m_run; sm_l[wave][col] = l_run; }
+#pragma unroll
+  for (int m = 0; m < VM; ++m)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sm_o[wave][16 * m + 4 * grp + i][col] = O[m][i];
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < DH * 16; idx += 256) {
+    const int e = idx >> 4, c = idx & 15;
+    const float M = fmaxf(fmaxf(sm_m[0][c], sm_m[1][c]), fmaxf(sm_m[2][c], sm_m[3][c]));
+    float num = 0.f, den = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float f = __expf(sm_m[w][c] - M);
+      num += f * sm_o[w][e][c];
+      den += f * sm_l[w][c];
+    }
+    a.o[d_frag_index(row0 + c, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
+  }
+}
+
+void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a) {
+  const dim3 grid(a.B * a.kv.H, a.P_pad / 16);
+  if (a.kv.dh == 64) hipLaunchKernelGGL(k_attention_rows<64>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(k_attention_rows<128>, grid, dim3(256), 0, s, a);
+}
+
+// ------------------------------------------------------------------ row kernels of the batched prompt
+__global__ __launch_bounds__(1024) void k_embed_ln_rows(const int32_t *tokens, const int32_t *start, const bf16_t *tok_emb,
+                                                        const bf16_t *pos_emb, const float *g, const float *bt, float *x,
+                                                        bf16_t *a_out, int B, int P, int P_pad, int d, int V) {
+  __shared__ float sh[16];
+  const int row = blockIdx.x, b = row / P_pad, col = row - b * P_pad, d4 = d >> 2;
+  if (col >= P) return;  // tile padding: rows stay zero
+  int tok = tokens[(long)col * B + b];
+  tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+  int pos = col - start[b];
+  if (pos < 0) pos = 0;
+  const uint2 *te = (const uint2 *)(tok_emb + (long)tok * d), *pe = (const uint2 *)(pos_emb + (long)pos * d);
+  floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i) {
+    const int c = (int)threadIdx.x + 1024 * i;
+    if (c < d4) {
+      const uint2 aa = te[c], p = pe[c];
+      gv[i] = ((const floatx4 *)g)[c];
+      bv[i] = ((const floatx4 *)bt)[c];
+      v[i] = floatx4{bf2f(aa.x & 0xffffu) + bf2f(p.x & 0xffffu), bf2f(aa.x >> 16) + bf2f(p.x >> 16),
+                     bf2f(aa.y & 0xffffu) + bf2f(p.y & 0xffffu), bf2f(aa.y >> 16) + bf2f(p.y >> 16)};
+      ((floatx4 *)x)[(long)row * d4 + c] = v[i];
+    }
+  }
+  ln_finish_row(v, gv, bv, d, row, a_out, sh);
+}
+
+__global__ __launch_bounds__(1024) void k_ln_rows(const float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
+  __shared__ float sh[16];
+  const int row = blockIdx.x, d4 = d >> 2;
+  floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
+#pragma unroll
+  for (int i = 0; i < LN_NC; ++i) {
+    const int c = (int)threadIdx.x + 1024 * i;
+    if (c < d4) {
+      v[i] = ((const floatx4 *)x)[(long)row * d4 + c];
+      gv[i] = ((const floatx4 *)g)[c];
+      bv[i] = ((const floatx4 *)bt)[c];
+    }
+  }
+  ln_finish_row(v, gv, bv, d, row, a_out, sh);
+}
+
+__global__ void k_gather_rows(const float *x_rows, float *x_out, int P_pad, int pos, int d) {
+  const long src = ((long)blockIdx.x * P_pad + pos) * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) x_out[(long)blockIdx.x * d + k] = x_rows[src + k];
+}
+
+void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, const int32_t *start, const bf16_t *tok_emb,
+                        const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int P,
+                        int P_pad, int d, int V) {
+  hipLaunchKernelGGL(k_embed_ln_rows, dim3(B * P_pad), dim3(1024), 0, s, tokens, start, tok_emb, pos_emb, g, b, x, a_out,
+                     B, P, P_pad, d, V);
+}
+void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b, bf16_t *a_out, int rows, int d) {
+  hipLaunchKernelGGL(k_ln_rows, dim3(rows), dim3(1024), 0, s, x, g, b, a_out, d);
+}
+void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, int B, int P_pad, int pos, int d) {
+  hipLaunchKernelGGL(k_gather_rows, dim3(B), dim3(256), 0, s, x_rows, x_out, P_pad, pos, d);
 }
 
 // ------------------------------------------------------------------ argmax over workgroup partials

@@ -84,6 +84,10 @@ struct skd_state {
   // plans (bf16)
   GemmPlan p_qkv, p_out, p_ffn1, p_ffn2, p_head;
   int max_split = 1, attn_splits = 1;
+  // batched prompt workspace (allocated by the first batched skd_prefill)
+  float *pf_x = nullptr;
+  bf16_t *pf_a = nullptr, *pf_q = nullptr, *pf_o = nullptr, *pf_u = nullptr;
+  int prefill_mode = 1;            // 1 = whole prompt per layer (bf16 path), 0 = column by column
   // sequencing
   bool prefilled = false, have_hidden = false, have_argmax = false;
   int steps_done = 0;
@@ -491,6 +495,7 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
     ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
     while (st->p_head.R > 1 && st->p_head.waves * st->p_head.R * (Bp / 16) > 64) --st->p_head.R;  // LM-head epilogue: one reduction stage
     if (st->p_head.waves * st->p_head.R * (Bp / 16) > 64) st->p_head.waves = 4;
+    st->prefill_mode = env_int("SKD_PREFILL_BATCHED", 1) != 0 ? 1 : 0;
     st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
     // split the key range of one head over several workgroups only when rows*heads alone cannot fill the chip
     int splits = 1;
@@ -546,6 +551,59 @@ extern "C" void skd_destroy(skd_state *st) {
   delete st;
 }
 
+// Whole prompt at once, layer by layer (Section 2.3: the prompt needs no generation, so it can be batched over
+// positions): activation rows are (sequence, position) pairs, the projections run on 128-row chunks, attention is
+// causal over the pages the QKV projection has just filled.
+static int prefill_batched(skd_state *st, const int32_t *cols) {
+  const skd_config &c = st->cfg;
+  const int B = c.batch, P = c.prompt_size, d = c.d_model, f = c.ffn, L = c.L;
+  const int P_pad = (P + 15) / 16 * 16;
+  const long rows = (long)B * P_pad, rows_pad = (rows + 127) / 128 * 128;
+  hipStream_t s = st->stream;
+  if (!st->pf_x) {
+    SKDCHECK(dev_alloc(st, &st->pf_x, (size_t)rows_pad * d));
+    SKDCHECK(dev_alloc(st, &st->pf_a, (size_t)rows_pad * d));
+    SKDCHECK(dev_alloc(st, &st->pf_q, (size_t)rows_pad * d));
+    SKDCHECK(dev_alloc(st, &st->pf_o, (size_t)rows_pad * d));
+    SKDCHECK(dev_alloc(st, &st->pf_u, (size_t)rows_pad * f));
+  }
+  // padding rows are read by the projections: keep them finite
+  HIPCHECK(hipMemsetAsync(st->pf_x, 0, (size_t)rows_pad * d * sizeof(float), s));
+  HIPCHECK(hipMemsetAsync(st->pf_a, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
+  HIPCHECK(hipMemsetAsync(st->pf_q, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
+  HIPCHECK(hipMemsetAsync(st->pf_o, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
+  bf16_embed_ln_rows(s, cols, st->start_dev, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, st->lw[0].ln1_g,
+                     st->lw[0].ln1_b, st->pf_x, st->pf_a, B, P, P_pad, d, c.vocab);
+  for (int l = 0; l < L; ++l) {
+    const LayerW &w = st->lw[l];
+    GemmArgs ga{};
+    ga.B = B; ga.B_pad = 128; ga.rows = (int)rows_pad; ga.P_pad = P_pad; ga.P = P; ga.kv = st->geom; ga.d = d; ga.split = 1;
+    ga.W = (const bf16_t *)w.wqkv; ga.A = st->pf_a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d;
+    ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
+    if (bf16_gemm(s, ga, EPI_QKV_ROWS, 3 * d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    AttnRowsArgs aa{};
+    aa.q = st->pf_q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
+    aa.B = B; aa.P_pad = P_pad; aa.P = P; aa.kv = st->geom; aa.o = st->pf_o;
+    bf16_attention_rows(s, aa);
+    ga.W = (const bf16_t *)w.wo; ga.A = st->pf_o; ga.bias = w.bo; ga.N = d; ga.K = d; ga.x = st->pf_x;
+    if (bf16_gemm(s, ga, EPI_RESID, d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    bf16_ln_rows(s, st->pf_x, w.ln2_g, w.ln2_b, st->pf_a, (int)rows, d);
+    ga.W = (const bf16_t *)w.w1; ga.A = st->pf_a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.act_out = st->pf_u;
+    if (bf16_gemm(s, ga, EPI_RELU, f % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    ga.W = (const bf16_t *)w.w2; ga.A = st->pf_u; ga.bias = w.b2; ga.N = d; ga.K = f; ga.x = st->pf_x;
+    if (bf16_gemm(s, ga, EPI_RESID, d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    if (l + 1 < L) bf16_ln_rows(s, st->pf_x, st->lw[l + 1].ln1_g, st->lw[l + 1].ln1_b, st->pf_a, (int)rows, d);
+    st->kv_len[l] = P;
+  }
+  // hidden state of the last prompt column, and its final LayerNorm, where the heads expect them
+  bf16_gather_rows(s, st->pf_x, st->x, B, P_pad, P - 1, d);
+  bf16_ln_rows(s, st->x, st->lnf_g, st->lnf_b, (bf16_t *)st->a, B, d);
+  HIPCHECK(hipGetLastError());
+  st->have_hidden = true;
+  st->have_argmax = false;
+  return SKD_OK;
+}
+
 extern "C" int skd_prefill(skd_state *st, const int32_t *tokens, const uint8_t *attn_mask) {
   if (!st || !tokens) return SKD_ERR_NULL;
   const skd_config &c = st->cfg;
@@ -581,10 +639,17 @@ extern "C" int skd_prefill(skd_state *st, const int32_t *tokens, const uint8_t *
   std::fill(st->kv_len.begin(), st->kv_len.end(), 0);
   st->prefilled = false;
   st->steps_done = 0;
-  for (int i = 0; i < P; ++i) {  // the prompt uses every layer, unless the caller's table decays into it
-    const int n = state_active_layers(st, i, st->layers_tmp.data());
-    if (n < 0) return n;
-    SKDCHECK(run_column(st, i, cols + (size_t)i * B, st->layers_tmp.data(), n));
+  bool full_depth_prompt = true;  // a caller's table may decay inside the prompt: then columns differ in depth
+  for (int i = 0; i < P && full_depth_prompt; ++i)
+    if (!st->n_table.empty() && st->n_table[i] != c.L) full_depth_prompt = false;
+  if (st->bf16 && st->prefill_mode == 1 && full_depth_prompt) {
+    SKDCHECK(prefill_batched(st, cols));
+  } else {
+    for (int i = 0; i < P; ++i) {  // column by column
+      const int n = state_active_layers(st, i, st->layers_tmp.data());
+      if (n < 0) return n;
+      SKDCHECK(run_column(st, i, cols + (size_t)i * B, st->layers_tmp.data(), n));
+    }
   }
   st->prefilled = true;
   if (!c.io_on_device) HIPCHECK(hipStreamSynchronize(st->stream));

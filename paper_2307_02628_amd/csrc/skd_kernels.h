@@ -47,7 +47,9 @@ enum GemmEpilogue {
   EPI_PARTIAL = 0,  // fp32 partial sums [split][B_pad][N], no bias
   EPI_QKV = 1,      // + bias; q -> row-major bf16, k/v -> KV page slot of position t
   EPI_RELU = 2,     // + bias, ReLU -> fragment-major bf16 [B_pad][N]
-  EPI_LOGITS = 3    // optional fp32 logits [B][N] + per-workgroup (max, argmax) partials
+  EPI_LOGITS = 3,   // optional fp32 logits [B][N] + per-workgroup (max, argmax) partials
+  EPI_QKV_ROWS = 4, // batched prompt: + bias; q -> fragment-major [rows][d]; k/v -> KV page slot of (sequence, position)
+  EPI_RESID = 5     // batched prompt: x[row][n] += value + bias (fp32 residual stream)
 };
 
 struct GemmArgs {
@@ -56,6 +58,11 @@ struct GemmArgs {
   const float *bias;   // [N] or null
   int N, K, B, B_pad;
   int split;           // workgroups along K (grid.y)
+  // batched prompt processing: activation rows are (sequence b, position pos) pairs, row = b * P_pad + pos,
+  // handled in chunks of B_pad rows along grid.z.  rows = 0: one chunk whose rows are the batch (decode).
+  int rows;            // B * P_pad
+  int P_pad, P;        // positions per sequence (padded to 16) and real prompt length
+  float *x;            // EPI_RESID: [rows][N] fp32
   // outputs (by epilogue)
   float *partial;      // EPI_PARTIAL
   bf16_t *q_out;       // EPI_QKV: [B_pad][d] row-major
@@ -93,6 +100,24 @@ struct AttnArgs {
   float *part;              // splits > 1: [splits][B*H][dh + 2]
 };
 void bf16_attention(hipStream_t s, const AttnArgs &a);
+// Causal attention of a whole prompt: query rows (b, pos), 16 positions per workgroup, keys start[b] .. pos.
+struct AttnRowsArgs {
+  const bf16_t *q;          // fragment-major [rows][d]
+  const bf16_t *pool;
+  const int32_t *bt_layer;  // [B][max_pages]
+  const int32_t *start;     // [B]
+  int B, P_pad, P;
+  KvGeom kv;
+  bf16_t *o;                // fragment-major [rows][d]
+};
+void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a);
+// Batched prompt row kernels: rows = B * P_pad, tokens laid out [P][B].
+void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, const int32_t *start, const bf16_t *tok_emb,
+                        const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int P,
+                        int P_pad, int d, int V);
+void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b, bf16_t *a_out, int rows, int d);
+// x_out[b][:] = x_rows[b * P_pad + pos][:]
+void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, int B, int P_pad, int pos, int d);
 void bf16_argmax_final(hipStream_t s, const float *pmax, const int32_t *pidx, int groups, int B_pad, int32_t *tokens,
                        int B);
 

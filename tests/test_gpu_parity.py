@@ -325,3 +325,41 @@ def test_rewind_regenerates_identically():
             dec.decode_step(16 + k, tape[k])
             np.testing.assert_array_equal(dec.logits_argmax()[1], first[k])
         assert [dec.kv_len(l) for l in range(4)] == lens
+
+
+def test_batched_prefill_matches_column_prefill():
+    # the whole-prompt path (row-chunked projections + causal prompt attention) against the column-by-column path:
+    # same cache contents up to bf16 rounding of differently ordered sums, same logits within the parity tolerance
+    import os
+    shape = MID
+    w = bf16_weights(shape, 2)
+    B, P, N = 5, 40, 60
+    pr = S.make_prompts(B, P, shape.V, 3)
+    mask = S.make_ragged_mask(B, P, 1, 40, seed=4)
+    mask[0] = 1
+    tape = S.make_token_tape(B, N - P, shape.V, 5)
+    outs = {}
+    for mode in ("1", "0"):
+        os.environ["SKD_PREFILL_BATCHED"] = mode
+        try:
+            cfg = skd.make_config(shape, B, P, N, 1, 3, page_tokens=32)
+            with skd.Decoder(cfg, w) as dec:
+                dec.prefill(pr, mask)
+                lg = [dec.logits_argmax()[1]]
+                kv = [dec.kv_read(l, b) for l in range(shape.L) for b in range(B)]
+                for k in range(N - P):
+                    dec.decode_step(P + k, tape[k])
+                    lg.append(dec.logits_argmax()[1])
+                outs[mode] = (np.stack(lg), kv, [dec.kv_len(l) for l in range(shape.L)])
+        finally:
+            os.environ.pop("SKD_PREFILL_BATCHED", None)
+    a, b = outs["1"], outs["0"]
+    assert a[2] == b[2]
+    rng = b[0].max() - b[0].min()
+    assert np.abs(a[0] - b[0]).max() / rng < 5e-3
+    start = (mask == 0).sum(axis=1)
+    for i, ((ka, va), (kb, vb)) in enumerate(zip(a[1], b[1])):
+        r = i % B
+        sl = slice(int(start[r]), P)                      # padded columns are never read: not compared
+        np.testing.assert_allclose(ka[sl], kb[sl], rtol=2e-2, atol=2e-2)
+        np.testing.assert_allclose(va[sl], vb[sl], rtol=2e-2, atol=2e-2)
