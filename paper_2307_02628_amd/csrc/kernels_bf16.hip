@@ -463,7 +463,9 @@ __global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
   __shared__ float sm_m[4], sm_l[4];
   __shared__ float sm_o[4][DH];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4;
-  const int H = a.kv.H, b = blockIdx.x / H, h = blockIdx.x % H, d = H * DH;
+  const int H = a.kv.H, h = blockIdx.x % H, d = H * DH;
+  // longest rows are dispatched first, so that the last workgroups to start are the short ones
+  const int b = a.order ? a.order[blockIdx.x / H] : (int)(blockIdx.x / H);
   const int j0 = a.start[b], t = a.t;
   const int blk_lo = j0 >> 5, blk_hi = (t >> 5) + 1;  // blocks [blk_lo, blk_hi)
   const int nblk = blk_hi - blk_lo;
@@ -563,7 +565,7 @@ __global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
       const float r = den > 0.f ? num / den : 0.f;
       a.o[d_frag_index(b, h * DH + e, d)] = (bf16_t)f2bf(r);
     } else {
-      float *pp = a.part + ((long)blockIdx.y * gridDim.x + blockIdx.x) * (DH + 2);
+      float *pp = a.part + ((long)blockIdx.y * gridDim.x + (long)b * H + h) * (DH + 2);
       pp[e] = num;
       if (e == 0) { pp[DH] = M; pp[DH + 1] = den; }
     }

@@ -68,6 +68,7 @@ struct skd_state {
   // per-step device buffers
   int32_t *tok_dev = nullptr;      // [B] input column
   int32_t *prompt_dev = nullptr;   // [P][B]
+  int32_t *order_dev = nullptr;    // [B] rows by descending real length (attention dispatch order)
   int32_t *start_dev = nullptr;    // [B] first real column
   int32_t *argmax_dev = nullptr;   // [B]
   float *u_dev = nullptr;          // [B] uniform numbers of the sampling head
@@ -375,7 +376,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U, st->p_qkv.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
       AttnArgs aa{};
-      aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
+      aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->order_dev;
       aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
@@ -477,7 +478,7 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   // ---- workspaces
   const int Bp = st->B_pad;
   auto A = [&](auto **p, size_t n) { if (rc == SKD_OK) rc = dev_alloc(st, p, n); };
-  A(&st->tok_dev, B); A(&st->prompt_dev, (size_t)c.prompt_size * B); A(&st->start_dev, B); A(&st->argmax_dev, B); A(&st->u_dev, B);
+  A(&st->tok_dev, B); A(&st->prompt_dev, (size_t)c.prompt_size * B); A(&st->start_dev, B); A(&st->order_dev, B); A(&st->argmax_dev, B); A(&st->u_dev, B);
   A(&st->x, (size_t)Bp * d);
   if (st->bf16) {
     st->p_qkv = plan_direct(3 * d, Bp);
@@ -549,6 +550,18 @@ extern "C" void skd_destroy(skd_state *st) {
   for (hipEvent_t e : st->prof_free) (void)hipEventDestroy(e);
   for (void *p : st->allocs) (void)hipFree(p);
   delete st;
+}
+
+// per-row padding offsets and the dispatch order of the attention workgroups (longest rows first)
+static int upload_start(skd_state *st, const std::vector<int32_t> &start) {
+  const int B = st->cfg.batch;
+  std::vector<int32_t> order(B);
+  for (int b = 0; b < B; ++b) order[b] = b;
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return start[x] < start[y]; });
+  HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
+  HIPCHECK(hipMemcpyAsync(st->order_dev, order.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
+  HIPCHECK(hipStreamSynchronize(st->stream));
+  return SKD_OK;
 }
 
 // Whole prompt at once, layer by layer (Section 2.3: the prompt needs no generation, so it can be batched over
@@ -634,8 +647,7 @@ extern "C" int skd_prefill(skd_state *st, const int32_t *tokens, const uint8_t *
     HIPCHECK(hipStreamSynchronize(st->stream));
     cols = st->prompt_dev;
   }
-  HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
-  HIPCHECK(hipStreamSynchronize(st->stream));
+  SKDCHECK(upload_start(st, start));
   std::fill(st->kv_len.begin(), st->kv_len.end(), 0);
   st->prefilled = false;
   st->steps_done = 0;
@@ -854,8 +866,7 @@ extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const
   if (rc != SKD_OK) return rc;
   std::vector<int32_t> start(B, 0);
   if (start_in) start.assign(start_in, start_in + B);
-  HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
-  HIPCHECK(hipStreamSynchronize(st->stream));
+  SKDCHECK(upload_start(st, start));
   st->prefilled = true;
   st->steps_done = cols - c.prompt_size;
   st->have_hidden = false;

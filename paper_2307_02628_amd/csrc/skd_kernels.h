@@ -93,6 +93,7 @@ struct AttnArgs {
   const bf16_t *pool;
   const int32_t *bt_layer;  // [B][max_pages]
   const int32_t *start;     // [B] first real column of each row
+  const int32_t *order;     // [B] rows sorted by descending length: workgroup x/H handles row order[x/H] (null = identity)
   int t;                    // keys start[b] .. t
   int B, splits;
   KvGeom kv;
