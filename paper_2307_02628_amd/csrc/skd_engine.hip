@@ -69,6 +69,7 @@ struct skd_state {
   int32_t *tok_dev = nullptr;      // [B] input column
   int32_t *prompt_dev = nullptr;   // [P][B]
   int32_t *order_dev = nullptr;    // [B] rows by descending real length (attention dispatch order)
+  bool ragged = false;             // rows differ in length: use order_dev
   int32_t *start_dev = nullptr;    // [B] first real column
   int32_t *argmax_dev = nullptr;   // [B]
   float *u_dev = nullptr;          // [B] uniform numbers of the sampling head
@@ -376,7 +377,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U, st->p_qkv.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
       AttnArgs aa{};
-      aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->order_dev;
+      aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->ragged ? st->order_dev : nullptr;
       aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
@@ -558,6 +559,7 @@ static int upload_start(skd_state *st, const std::vector<int32_t> &start) {
   std::vector<int32_t> order(B);
   for (int b = 0; b < B; ++b) order[b] = b;
   std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return start[x] < start[y]; });
+  st->ragged = *std::max_element(start.begin(), start.end()) != *std::min_element(start.begin(), start.end());
   HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
   HIPCHECK(hipMemcpyAsync(st->order_dev, order.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
   HIPCHECK(hipStreamSynchronize(st->stream));
