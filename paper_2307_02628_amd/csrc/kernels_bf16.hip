@@ -160,7 +160,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
   // of consecutive addresses from each of its R weight-row streams.
   const int kw0 = (int)((long)Kf * blockIdx.y / a.split), kw1 = (int)((long)Kf * (blockIdx.y + 1) / a.split);
   const int nbuf = (kw1 - kw0) / U;  // the launcher picks U so that this is exact
-  const bf16x8 *Wb = (const bf16x8 *)a.W + ((long)blockIdx.x * R * Kf + kw0) * 64 + lane;
+  // weight tile T lives in tile group T / G at slot T % G; the G tiles of a group alternate per k-step
+  const bf16x8 *Wl = (const bf16x8 *)a.W + lane;
+  const long kstride = (long)a.G * 64;
+  long woff[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int T = blockIdx.x * R + r;
+    woff[r] = (((long)(T / a.G) * Kf + kw0) * a.G + T % a.G) * 64;
+  }
   const int row0 = blockIdx.z * (MB * 16);  // chunk of activation rows (0 when decoding)
   const bf16x8 *Ab = (const bf16x8 *)a.A + ((long)blockIdx.z * MB * Kf + kw0) * 64 + lane;
 
@@ -175,7 +183,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) w[u][r] = Wb[((long)r * Kf + j * U + u) * 64];
+      for (int r = 0; r < R; ++r) w[u][r] = Wl[woff[r] + (long)(j * U + u) * kstride];
 #pragma unroll
       for (int m = 0; m < MB; ++m) x[u][m] = Ab[((long)m * Kf + j * U + u) * 64];
     }
@@ -332,7 +340,7 @@ static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int 
 // Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}.
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves) {
   const int MB = a.B_pad / 16;
-  if (R < 1 || R > 4 || (waves != 4 && waves != 8) || MB < 1 || MB > 8) return -1;
+  if (R < 1 || R > 4 || a.G < 1 || a.G > 4 || (waves != 4 && waves != 8) || MB < 1 || MB > 8) return -1;
   // the LM-head epilogue keeps all tile rows of the workgroup in the 64 KiB reduction buffer (the caller sizes
   // its argmax partials by R, so R is never changed here)
   if (epi == EPI_LOGITS && waves * R * MB > 64) return -1;
@@ -813,12 +821,12 @@ __device__ inline float src_to_f<bf16_t>(const bf16_t *p, long i) { return bf2f(
 
 // one thread per 8-element lane slot of the destination
 template <typename T>
-__global__ void k_prep_frag(const T *src, bf16_t *dst, long N, long K, long N_pad) {
+__global__ void k_prep_frag(const T *src, bf16_t *dst, long N, long K, long N_pad, int G) {
   const long slot = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const long Kf = K >> 5;
   if (slot >= (N_pad >> 4) * Kf * 64) return;
   const int lane = slot & 63;
-  const long frag = slot >> 6, kf = frag % Kf, nt = frag / Kf;
+  const long frag = slot >> 6, kf = (frag / G) % Kf, nt = frag / (G * Kf) * G + frag % G;
   const long row = nt * 16 + (lane & 15), col = kf * 32 + (lane >> 4) * 8;
   uint32_t pk[4] = {0, 0, 0, 0};
   if (row < N)
@@ -835,11 +843,12 @@ __global__ void k_prep_f32(const T *src, float *dst, long n) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = src_to_f<T>(src, i);
 }
-void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long N, long K, long N_pad) {
+void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long N, long K, long N_pad,
+                      int G) {
   const long slots = (N_pad / 16) * (K / 32) * 64;
   const dim3 grid((unsigned)((slots + 255) / 256));
-  if (src_is_bf16) hipLaunchKernelGGL(k_prep_frag<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, N, K, N_pad);
-  else hipLaunchKernelGGL(k_prep_frag<float>, grid, dim3(256), 0, s, (const float *)src, dst, N, K, N_pad);
+  if (src_is_bf16) hipLaunchKernelGGL(k_prep_frag<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, N, K, N_pad, G);
+  else hipLaunchKernelGGL(k_prep_frag<float>, grid, dim3(256), 0, s, (const float *)src, dst, N, K, N_pad, G);
 }
 void prep_matrix_rm_bf16(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long n) {
   const dim3 grid((unsigned)((n + 255) / 256));

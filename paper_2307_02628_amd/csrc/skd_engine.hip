@@ -162,8 +162,9 @@ int upload_vec(skd_state *st, const skd_weights &w, const void *src, size_t n, v
   return SKD_OK;
 }
 
-// matrix [N][K]: fp32 path -> fp32 row-major; bf16 path -> fragment-major (frag) or row-major bf16
-int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, long K, void *staging, bool frag,
+// matrix [N][K]: fp32 path -> fp32 row-major; bf16 path -> fragment-major (frag > 0) or row-major bf16
+// (frag = tile-group size of the fragment-major layout, 0 = row-major)
+int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, long K, void *staging, int frag,
                void **out) {
   const void *dsrc = nullptr;
   SKDCHECK(stage(st, w, src, (size_t)N * K, staging, &dsrc));
@@ -176,7 +177,7 @@ int upload_mat(skd_state *st, const skd_weights &w, const void *src, long N, lon
     const long N_pad = (N + 191) / 192 * 192;  // whole groups of 1..4 tiles: no wave tile ever leaves the buffer
     bf16_t *p = nullptr;
     SKDCHECK(dev_alloc(st, &p, (size_t)N_pad * K));
-    prep_matrix_frag(st->stream, dsrc, w.elem == SKD_W_BF16, p, N, K, N_pad);
+    prep_matrix_frag(st->stream, dsrc, w.elem == SKD_W_BF16, p, N, K, N_pad, frag);
     *out = p;
   } else {
     bf16_t *p = nullptr;
@@ -372,7 +373,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       GemmArgs ga{};
       ga.B = B; ga.B_pad = st->B_pad; ga.kv = st->geom; ga.t = t; ga.d = d;
       // q, k, v projection; k and v go straight into this layer's page slot for column t
-      ga.W = (const bf16_t *)w.wqkv; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
+      ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
       ga.q_out = q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
       { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U, st->p_qkv.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
@@ -381,14 +382,14 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
-      ga.W = (const bf16_t *)w.wo; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
+      ga.W = (const bf16_t *)w.wo; ga.G = st->p_out.R; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
       { ProfScope ps_(st, SKD_PROF_GEMM_OUT); grc = bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R, st->p_out.U, st->p_out.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
       { ProfScope ps_(st, SKD_PROF_REDUCE_LN); bf16_reduce_ln(s, st->partial, st->p_out.split, st->B_pad, w.bo, st->x, w.ln2_g, w.ln2_b, a, B, d); }
-      ga.W = (const bf16_t *)w.w1; ga.A = a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.split = 1; ga.act_out = u;
+      ga.W = (const bf16_t *)w.w1; ga.G = st->p_ffn1.R; ga.A = a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.split = 1; ga.act_out = u;
       { ProfScope ps_(st, SKD_PROF_GEMM_FFN1); grc = bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R, st->p_ffn1.U, st->p_ffn1.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
-      ga.W = (const bf16_t *)w.w2; ga.A = u; ga.N = d; ga.K = f; ga.split = st->p_ffn2.split;
+      ga.W = (const bf16_t *)w.w2; ga.G = st->p_ffn2.R; ga.A = u; ga.N = d; ga.K = f; ga.split = st->p_ffn2.split;
       { ProfScope ps_(st, SKD_PROF_GEMM_FFN2); grc = bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R, st->p_ffn2.U, st->p_ffn2.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
       // the reducer of the last sub-block already applies the next LayerNorm:
@@ -442,6 +443,26 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   while (st->B_pad < B) st->B_pad *= 2;
   st->layers_tmp.resize(L);
 
+  // ---- launch shapes (the weight layout below depends on them)
+  auto ov = [&](const char *name, int &v, int lo, int hi) { const int e = env_int(name, 0); if (e >= lo && e <= hi) v = e; };
+  if (st->bf16) {
+    const int Bp = st->B_pad;
+    st->p_qkv = plan_direct(3 * d, Bp);
+    st->p_ffn1 = plan_direct(f, Bp);
+    st->p_head = plan_direct(V, Bp);
+    st->p_out = plan_split(d, d, Bp);
+    st->p_ffn2 = plan_split(d, f, Bp);
+    ov("SKD_R_QKV", st->p_qkv.R, 1, 4); ov("SKD_R_FFN1", st->p_ffn1.R, 1, 4); ov("SKD_R_HEAD", st->p_head.R, 1, 4);
+    ov("SKD_R_OUT", st->p_out.R, 1, 4); ov("SKD_R_FFN2", st->p_ffn2.R, 1, 4);
+    ov("SKD_S_OUT", st->p_out.split, 1, 32); ov("SKD_S_FFN2", st->p_ffn2.split, 1, 32);
+    ov("SKD_U_QKV", st->p_qkv.U, 1, 4); ov("SKD_U_FFN1", st->p_ffn1.U, 1, 4); ov("SKD_U_HEAD", st->p_head.U, 1, 4);
+    ov("SKD_U_OUT", st->p_out.U, 1, 4); ov("SKD_U_FFN2", st->p_ffn2.U, 1, 4);
+    ov("SKD_W_QKV", st->p_qkv.waves, 4, 8); ov("SKD_W_FFN1", st->p_ffn1.waves, 4, 8); ov("SKD_W_HEAD", st->p_head.waves, 4, 8);
+    ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
+    while (st->p_head.R > 1 && st->p_head.waves * st->p_head.R * (Bp / 16) > 64) --st->p_head.R;  // LM-head epilogue: one reduction stage
+    if (st->p_head.waves * st->p_head.R * (Bp / 16) > 64) st->p_head.waves = 4;
+  }
+
   // ---- weights
   const size_t esz = w->elem == SKD_W_BF16 ? 2 : 4;
   size_t biggest = std::max({(size_t)V * d, (size_t)c.max_pos * d, (size_t)3 * d * d, (size_t)f * d});
@@ -452,10 +473,10 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   }
   int rc = SKD_OK;
   auto vec = [&](const void *src, size_t n, float **o) { if (rc == SKD_OK) rc = upload_vec(st, *w, src, n, staging, o); };
-  auto mat = [&](const void *src, long N, long K, bool frag, void **o) { if (rc == SKD_OK) rc = upload_mat(st, *w, src, N, K, staging, frag, o); };
-  mat(w->tok_emb, V, d, false, &st->tok_emb);
-  mat(w->pos_emb, c.max_pos, d, false, &st->pos_emb);
-  if (st->bf16 || w->lm_head) mat(w->lm_head ? w->lm_head : w->tok_emb, V, d, true, &st->head);
+  auto mat = [&](const void *src, long N, long K, int frag, void **o) { if (rc == SKD_OK) rc = upload_mat(st, *w, src, N, K, staging, frag, o); };
+  mat(w->tok_emb, V, d, 0, &st->tok_emb);
+  mat(w->pos_emb, c.max_pos, d, 0, &st->pos_emb);
+  if (st->bf16 || w->lm_head) mat(w->lm_head ? w->lm_head : w->tok_emb, V, d, st->bf16 ? st->p_head.R : 1, &st->head);
   else st->head = st->tok_emb;
   vec(w->lnf_g, d, &st->lnf_g);
   vec(w->lnf_b, d, &st->lnf_b);
@@ -463,11 +484,11 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   for (int l = 0; l < L && rc == SKD_OK; ++l) {
     LayerW &lw = st->lw[l];
     vec(w->ln1_g[l], d, &lw.ln1_g); vec(w->ln1_b[l], d, &lw.ln1_b);
-    mat(w->wqkv[l], 3L * d, d, true, &lw.wqkv); vec(w->bqkv[l], 3 * (size_t)d, &lw.bqkv);
-    mat(w->wo[l], d, d, true, &lw.wo); vec(w->bo[l], d, &lw.bo);
+    mat(w->wqkv[l], 3L * d, d, st->p_qkv.R, &lw.wqkv); vec(w->bqkv[l], 3 * (size_t)d, &lw.bqkv);
+    mat(w->wo[l], d, d, st->p_out.R, &lw.wo); vec(w->bo[l], d, &lw.bo);
     vec(w->ln2_g[l], d, &lw.ln2_g); vec(w->ln2_b[l], d, &lw.ln2_b);
-    mat(w->w1[l], f, d, true, &lw.w1); vec(w->b1[l], f, &lw.b1);
-    mat(w->w2[l], d, f, true, &lw.w2); vec(w->b2[l], d, &lw.b2);
+    mat(w->w1[l], f, d, st->p_ffn1.R, &lw.w1); vec(w->b1[l], f, &lw.b1);
+    mat(w->w2[l], d, f, st->p_ffn2.R, &lw.w2); vec(w->b2[l], d, &lw.b2);
   }
   if (staging) (void)hipFree(staging);
   if (rc != SKD_OK) return fail(rc);
@@ -482,21 +503,6 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   A(&st->tok_dev, B); A(&st->prompt_dev, (size_t)c.prompt_size * B); A(&st->start_dev, B); A(&st->order_dev, B); A(&st->argmax_dev, B); A(&st->u_dev, B);
   A(&st->x, (size_t)Bp * d);
   if (st->bf16) {
-    st->p_qkv = plan_direct(3 * d, Bp);
-    st->p_ffn1 = plan_direct(f, Bp);
-    st->p_head = plan_direct(V, Bp);
-    st->p_out = plan_split(d, d, Bp);
-    st->p_ffn2 = plan_split(d, f, Bp);
-    auto ov = [&](const char *name, int &v, int lo, int hi) { const int e = env_int(name, 0); if (e >= lo && e <= hi) v = e; };
-    ov("SKD_R_QKV", st->p_qkv.R, 1, 4); ov("SKD_R_FFN1", st->p_ffn1.R, 1, 4); ov("SKD_R_HEAD", st->p_head.R, 1, 4);
-    ov("SKD_R_OUT", st->p_out.R, 1, 4); ov("SKD_R_FFN2", st->p_ffn2.R, 1, 4);
-    ov("SKD_S_OUT", st->p_out.split, 1, 32); ov("SKD_S_FFN2", st->p_ffn2.split, 1, 32);
-    ov("SKD_U_QKV", st->p_qkv.U, 1, 4); ov("SKD_U_FFN1", st->p_ffn1.U, 1, 4); ov("SKD_U_HEAD", st->p_head.U, 1, 4);
-    ov("SKD_U_OUT", st->p_out.U, 1, 4); ov("SKD_U_FFN2", st->p_ffn2.U, 1, 4);
-    ov("SKD_W_QKV", st->p_qkv.waves, 4, 8); ov("SKD_W_FFN1", st->p_ffn1.waves, 4, 8); ov("SKD_W_HEAD", st->p_head.waves, 4, 8);
-    ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
-    while (st->p_head.R > 1 && st->p_head.waves * st->p_head.R * (Bp / 16) > 64) --st->p_head.R;  // LM-head epilogue: one reduction stage
-    if (st->p_head.waves * st->p_head.R * (Bp / 16) > 64) st->p_head.waves = 4;
     st->prefill_mode = env_int("SKD_PREFILL_BATCHED", 1) != 0 ? 1 : 0;
     st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
     // split the key range of one head over several workgroups only when rows*heads alone cannot fill the chip
@@ -593,19 +599,19 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
     const LayerW &w = st->lw[l];
     GemmArgs ga{};
     ga.B = B; ga.B_pad = 128; ga.rows = (int)rows_pad; ga.P_pad = P_pad; ga.P = P; ga.kv = st->geom; ga.d = d; ga.split = 1;
-    ga.W = (const bf16_t *)w.wqkv; ga.A = st->pf_a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d;
+    ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = st->pf_a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d;
     ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
     if (bf16_gemm(s, ga, EPI_QKV_ROWS, 3 * d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
     AttnRowsArgs aa{};
     aa.q = st->pf_q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
     aa.B = B; aa.P_pad = P_pad; aa.P = P; aa.kv = st->geom; aa.o = st->pf_o;
     bf16_attention_rows(s, aa);
-    ga.W = (const bf16_t *)w.wo; ga.A = st->pf_o; ga.bias = w.bo; ga.N = d; ga.K = d; ga.x = st->pf_x;
+    ga.W = (const bf16_t *)w.wo; ga.G = st->p_out.R; ga.A = st->pf_o; ga.bias = w.bo; ga.N = d; ga.K = d; ga.x = st->pf_x;
     if (bf16_gemm(s, ga, EPI_RESID, d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
     bf16_ln_rows(s, st->pf_x, w.ln2_g, w.ln2_b, st->pf_a, (int)rows, d);
-    ga.W = (const bf16_t *)w.w1; ga.A = st->pf_a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.act_out = st->pf_u;
+    ga.W = (const bf16_t *)w.w1; ga.G = st->p_ffn1.R; ga.A = st->pf_a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.act_out = st->pf_u;
     if (bf16_gemm(s, ga, EPI_RELU, f % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
-    ga.W = (const bf16_t *)w.w2; ga.A = st->pf_u; ga.bias = w.b2; ga.N = d; ga.K = f; ga.x = st->pf_x;
+    ga.W = (const bf16_t *)w.w2; ga.G = st->p_ffn2.R; ga.A = st->pf_u; ga.bias = w.b2; ga.N = d; ga.K = f; ga.x = st->pf_x;
     if (bf16_gemm(s, ga, EPI_RESID, d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
     if (l + 1 < L) bf16_ln_rows(s, st->pf_x, st->lw[l + 1].ln1_g, st->lw[l + 1].ln1_b, st->pf_a, (int)rows, d);
     st->kv_len[l] = P;
@@ -709,7 +715,7 @@ static int head_logits(skd_state *st, float *logits_target) {
     { ProfScope ps_(st, SKD_PROF_OTHER); f32_argmax(s, lg, st->argmax_dev, B, V); }
   } else {
     GemmArgs ga{};
-    ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
+    ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.G = st->p_head.R; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
     ga.N = V; ga.K = d; ga.split = 1; ga.logits = logits_target; ga.pmax = st->pmax; ga.pidx = st->pidx;
     int groups = 0;
     { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves); }

@@ -39,6 +39,10 @@ int sample_top_p(hipStream_t s, const float *logits, int B, int V, float tempera
 // fragments stored as 64 lanes x 8 elements, lane = (row % 16) + 16 * ((col % 32) / 8),
 // element = col % 8, fragments ordered [row / 16][col / 32].  One fragment is
 // exactly what one lane-wide 16-byte load feeds to v_mfma_f32_16x16x32_bf16.
+// Weight matrices refine the fragment order: the 16-row tiles are bundled in
+// groups of G (1..4, chosen per matrix as the tile rows one workgroup owns) and
+// stored [tile / G][col / 32][tile % G], so that the G fragments a wave needs for
+// one k-step are G KiB of consecutive addresses.  Activations use G = 1.
 inline long frag_index(long row, long col, long K) {
   return (((row / 16) * (K / 32) + col / 32) * 64 + (row % 16) + 16 * ((col % 32) / 8)) * 8 + col % 8;
 }
@@ -53,7 +57,8 @@ enum GemmEpilogue {
 };
 
 struct GemmArgs {
-  const bf16_t *W;     // fragment-major [Nt_pad*16][K]
+  const bf16_t *W;     // fragment-major [Nt_pad*16][K], tiles in groups of G
+  int G;               // tile-group size of W's layout (Nt_pad is a multiple of 12, so of every G)
   const bf16_t *A;     // fragment-major [B_pad][K]
   const float *bias;   // [N] or null
   int N, K, B, B_pad;
@@ -123,7 +128,8 @@ void bf16_argmax_final(hipStream_t s, const float *pmax, const int32_t *pidx, in
                        int B);
 
 // weight preparation (source fp32 or bf16 row-major, on device)
-void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long N, long K, long N_pad);
+void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long N, long K, long N_pad,
+                      int G);
 void prep_matrix_rm_bf16(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long n);
 void prep_to_f32(hipStream_t s, const void *src, int src_is_bf16, float *dst, long n);
 // KV debug hooks: [B][cols][d] fp32 <-> pages
