@@ -142,6 +142,15 @@ def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, war
             else:
                 rec["bytes"] = sum(layers[:steps]) * class_bytes(shape, cls, 0)
         out["profile"] = prof
+        # step time against the number of active layers: one event pair per step
+        dec.rewind(P)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        evs[0].record(stream)
+        for k in range(steps):
+            run(k, k + 1)
+            evs[k + 1].record(stream)
+        torch.cuda.synchronize()
+        out["step_ms"] = [evs[k].elapsed_time(evs[k + 1]) for k in range(steps)]
     dec.close()
     del dec
     torch.cuda.synchronize()
@@ -254,6 +263,18 @@ def main():
         res["speedup_vs_full_depth"] = tok_s / ftok
         res["ideal_layer_ratio"] = shape.L * steps / sum(skip["layers"])
         res["ideal_byte_ratio"] = full["bytes"] / skip["bytes"]
+    if "step_ms" in skip:
+        ns = np.array(skip["layers"], dtype=np.float64)
+        ms = np.array(skip["step_ms"], dtype=np.float64)
+        by_n = {int(n): round(float(ms[ns == n].mean()), 4) for n in sorted(set(ns.tolist()), reverse=True)}
+        fit = {}
+        if len(by_n) > 1:
+            slope, icpt = np.polyfit(ns, ms, 1)
+            resid = ms - (slope * ns + icpt)
+            fit = {"ms_per_active_layer": float(slope), "ms_fixed": float(icpt),
+                   "r2": float(1.0 - resid.var() / ms.var())}
+        res["step_ms_by_active_layers"] = by_n
+        res["step_ms_linear_fit"] = fit
     roof = None
     if "profile" in skip:
         prof = {k: v for k, v in skip["profile"].items() if v["launches"]}

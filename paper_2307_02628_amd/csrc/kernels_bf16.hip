@@ -71,43 +71,64 @@ __device__ inline long kv_v_off(int h, int tt, int e, const KvGeom &g) {
 // the workgroup's K range among themselves; grid.y splits K further across
 // workgroups.  Each wave streams R weight-fragment rows and MB activation
 // fragments per 32-wide k-step through two register buffers of U k-steps.
+// What an epilogue reads from global memory (bias, residual, page index) is
+// fetched ahead of the cross-wave reduction, so the end of the kernel is not a
+// chain of dependent round trips.
+struct EpiPre {
+  floatx4 bias, x;
+  int page;
+};
 template <int EPI>
-__device__ inline void gemm_epilogue(const GemmArgs &a, int b, int n0, floatx4 v, int grp);
+__device__ inline EpiPre epi_prefetch(const GemmArgs &a, int row, int n0) {
+  EpiPre p;
+  p.bias = p.x = floatx4{0.f, 0.f, 0.f, 0.f};
+  p.page = 0;
+  if constexpr (EPI == EPI_QKV || EPI == EPI_RELU || EPI == EPI_QKV_ROWS || EPI == EPI_RESID) {
+    if (n0 + 3 < a.N) p.bias = *(const floatx4 *)&a.bias[n0];  // N is a multiple of 4 for these
+  }
+  if constexpr (EPI == EPI_QKV_ROWS) {
+    const int b = row / a.P_pad, pos = row - b * a.P_pad;
+    if (n0 >= a.d && n0 < a.N && row < a.rows && b < a.B && pos < a.P)
+      p.page = a.bt_layer[(long)b * a.kv.max_pages + pos / a.kv.page_tokens];
+  }
+  if constexpr (EPI == EPI_RESID) {
+    if (n0 + 3 < a.N && row < a.rows) p.x = *(const floatx4 *)&a.x[(long)row * a.N + n0];
+  }
+  return p;
+}
+
+template <int EPI>
+__device__ inline void gemm_epilogue(const GemmArgs &a, int b, int n0, floatx4 v, const EpiPre &pre);
 
 template <>
-__device__ inline void gemm_epilogue<EPI_PARTIAL>(const GemmArgs &a, int b, int n0, floatx4 v, int) {
+__device__ inline void gemm_epilogue<EPI_PARTIAL>(const GemmArgs &a, int b, int n0, floatx4 v, const EpiPre &) {
   if (n0 + 3 < a.N) {
     *(floatx4 *)&a.partial[((long)blockIdx.y * a.B_pad + b) * a.N + n0] = v;
   }
 }
 
 template <>
-__device__ inline void gemm_epilogue<EPI_QKV>(const GemmArgs &a, int b, int n0, floatx4 v, int) {
+__device__ inline void gemm_epilogue<EPI_QKV>(const GemmArgs &a, int b, int n0, floatx4 v, const EpiPre &pre) {
   if (n0 >= a.N) return;
-  for (int i = 0; i < 4; ++i) v[i] += a.bias[n0 + i];
+  v += pre.bias;
   const int which = n0 / a.d, within = n0 - which * a.d;
   if (which == 0) {
     uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
     *(uint2 *)&a.q_out[(long)b * a.d + within] = pk;
     return;
   }
-  if (b >= a.B) return;  // padded batch rows own no KV pages
-  const int h = within / a.kv.dh, e = within - h * a.kv.dh;
-  const int page = a.bt_layer[(long)b * a.kv.max_pages + a.t / a.kv.page_tokens];
-  bf16_t *pg = a.kv_pool + (long)page * a.kv.page_elems;
-  const int tt = a.t % a.kv.page_tokens;
-  if (which == 1) {
-    uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
-    *(uint2 *)&pg[kv_k_off(h, tt, e, a.kv)] = pk;  // 4 consecutive head-dim elements share one lane slot
-  } else {
-    for (int i = 0; i < 4; ++i) pg[kv_v_off(h, tt, e + i, a.kv)] = (bf16_t)f2bf(v[i]);
-  }
+  // k and v of the new position: row-major staging [B][k | v][d]; the attention kernel that follows
+  // files them into the KV page while it streams the cache (scattered 2- and 8-byte stores at the end of this
+  // kernel cost 3 us per layer)
+  if (b >= a.B) return;
+  uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+  *(uint2 *)&a.kv_new[((long)b * 2 + (which - 1)) * a.d + within] = pk;
 }
 
 template <>
-__device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0, floatx4 v, int) {
+__device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0, floatx4 v, const EpiPre &pre) {
   if (n0 >= a.N) return;
-  for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i] + a.bias[n0 + i], 0.f);
+  for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i] + pre.bias[i], 0.f);
   uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
   *(uint2 *)&a.act_out[d_frag_index(b, n0, a.N)] = pk;
 }
@@ -119,11 +140,11 @@ constexpr int gemm_stage_rows(int waves, int R, int MB) {
 }
 
 template <>
-__device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, int n0, floatx4 v, int) {
+__device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, int n0, floatx4 v, const EpiPre &pre) {
   if (n0 >= a.N || row >= a.rows) return;
   const int b = row / a.P_pad, pos = row - b * a.P_pad;
   if (b >= a.B || pos >= a.P) return;  // padding rows (of the 16-position tiles, of the last 128-row chunk)
-  for (int i = 0; i < 4; ++i) v[i] += a.bias[n0 + i];
+  v += pre.bias;
   const int which = n0 / a.d, within = n0 - which * a.d;
   const uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
   if (which == 0) {
@@ -131,8 +152,7 @@ __device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, i
     return;
   }
   const int h = within / a.kv.dh, e = within - h * a.kv.dh;
-  const int page = a.bt_layer[(long)b * a.kv.max_pages + pos / a.kv.page_tokens];
-  bf16_t *pg = a.kv_pool + (long)page * a.kv.page_elems;
+  bf16_t *pg = a.kv_pool + (long)pre.page * a.kv.page_elems;
   const int tt = pos % a.kv.page_tokens;
   if (which == 1) {
     *(uint2 *)&pg[kv_k_off(h, tt, e, a.kv)] = pk;
@@ -142,11 +162,9 @@ __device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, i
 }
 
 template <>
-__device__ inline void gemm_epilogue<EPI_RESID>(const GemmArgs &a, int row, int n0, floatx4 v, int) {
+__device__ inline void gemm_epilogue<EPI_RESID>(const GemmArgs &a, int row, int n0, floatx4 v, const EpiPre &pre) {
   if (n0 + 3 >= a.N || row >= a.rows) return;
-  floatx4 *xp = (floatx4 *)&a.x[(long)row * a.N + n0];
-  const floatx4 bias = *(const floatx4 *)&a.bias[n0];
-  *xp = *xp + (v + bias);
+  *(floatx4 *)&a.x[(long)row * a.N + n0] = pre.x + (v + pre.bias);
 }
 
 template <int MB, int R, int EPI, int U, int WAVES>
@@ -198,6 +216,23 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
           acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u][r], x[u][m], acc[r][m], 0, 0, 0);
   };
 
+  // epilogue operands of the (tile row, batch tile) pairs this wave will finish: fetched now when they are few,
+  // else at the start of each reduction stage
+  constexpr int RS = gemm_stage_rows(WAVES, R, MB);
+  constexpr int NP = (RS * MB + WAVES - 1) / WAVES;
+  constexpr bool EARLY = RS == R && NP <= 2;
+  EpiPre pre[NP];
+  auto fetch_pre = [&](int r0) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = wave + i * WAVES;
+      const int r = r0 + p / MB, m = p % MB;
+      if (p < RS * MB && r < R)
+        pre[i] = epi_prefetch<EPI>(a, row0 + m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4));
+    }
+  };
+  if constexpr (EARLY) fetch_pre(0);
+
   // two register buffers: the loads of one are in flight while the MFMAs of the other issue
   int j = wave;
   if (j < nbuf) {
@@ -216,23 +251,25 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
 
   // sum the waves' partial tiles in a fixed order (deterministic).  The LDS buffer holds RS of the R tile rows
   // at a time (64 KiB at most), so wide batches reduce in stages.
-  constexpr int RS = gemm_stage_rows(WAVES, R, MB);
   if constexpr (EPI != EPI_LOGITS) {
 #pragma unroll
     for (int r0 = 0; r0 < R; r0 += RS) {
       if (r0) __syncthreads();  // the previous stage has been consumed
+      if constexpr (!EARLY) fetch_pre(r0);
 #pragma unroll
       for (int rr = 0; rr < RS; ++rr)
 #pragma unroll
         for (int m = 0; m < MB; ++m)
           if (r0 + rr < R) red[(wave * (RS * MB) + rr * MB + m) * 64 + lane] = acc[r0 + rr < R ? r0 + rr : 0][m];
       __syncthreads();
-      for (int p = wave; p < RS * MB; p += WAVES) {
+#pragma unroll
+      for (int i = 0; i < NP; ++i) {
+        const int p = wave + i * WAVES;
         const int r = r0 + p / MB, m = p % MB;
-        if (r < R) {
+        if (p < RS * MB && r < R) {
           floatx4 v = red[p * 64 + lane];
           for (int w = 1; w < WAVES; ++w) v += red[(w * (RS * MB) + p) * 64 + lane];
-          gemm_epilogue<EPI>(a, row0 + m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, blockIdx.x);
+          gemm_epilogue<EPI>(a, row0 + m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, pre[i]);
         }
       }
     }
@@ -466,16 +503,16 @@ void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, c
 // Online softmax per wave in fp32; the four waves (and, with splits > 1, the
 // workgroups of one head) are merged with the usual max / sum rescaling.
 template <int DH>
-__global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
+__global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
   constexpr int QC = DH / 32, VM = DH / 16;
-  __shared__ float sm_m[4], sm_l[4];
+  __shared__ float sm_m[4], sm_l[4], sm_dot[4];
   __shared__ float sm_o[4][DH];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4;
   const int H = a.kv.H, h = blockIdx.x % H, d = H * DH;
   // longest rows are dispatched first, so that the last workgroups to start are the short ones
   const int b = a.order ? a.order[blockIdx.x / H] : (int)(blockIdx.x / H);
   const int j0 = a.start[b], t = a.t;
-  const int blk_lo = j0 >> 5, blk_hi = (t >> 5) + 1;  // blocks [blk_lo, blk_hi)
+  const int blk_lo = j0 >> 5, blk_hi = (t + 31) >> 5;  // blocks [blk_lo, blk_hi) hold the cached keys j0 .. t-1
   const int nblk = blk_hi - blk_lo;
   const int per = (nblk + a.splits - 1) / a.splits;
   const int my_lo = blk_lo + (int)blockIdx.y * per;
@@ -488,6 +525,25 @@ __global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
 #pragma unroll
   for (int c = 0; c < QC; ++c)
     qf[c] = *(const bf16x8 *)&a.q[(long)b * d + h * DH + 32 * c + 8 * grp];
+
+  // Position t itself is not in the cache yet: its k and v arrive in the projection's staging rows.  Thread e
+  // takes element e of q, k_t and v_t; the token joins the softmax as one more partial state when the waves
+  // are merged, and is filed into its page slot at the very end: nothing in this kernel reads that slot, and
+  // the lines around it have just been read, so the small stores hit lines that are resident in L2 (the same
+  // stores from the projection's epilogue or from a later kernel cost about 3 us per layer).
+  const bool with_new = blockIdx.y == gridDim.y - 1 && t >= j0;
+  float q_e = 0.f, k_e = 0.f, v_e = 0.f;
+  bf16_t k_bits = 0, v_bits = 0;
+  int page_t = 0;
+  if (with_new && threadIdx.x < DH) {
+    const bf16_t *kr = a.kv_new + ((long)b * 2) * d + h * DH;
+    k_bits = kr[threadIdx.x];
+    v_bits = kr[d + threadIdx.x];
+    q_e = bf2f(a.q[(long)b * d + h * DH + threadIdx.x]);
+    k_e = bf2f(k_bits);
+    v_e = bf2f(v_bits);
+    page_t = bt_row[t / a.kv.page_tokens];
+  }
 
   floatx4 O[VM];
 #pragma unroll
@@ -522,7 +578,7 @@ __global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int key = blk * 32 + 16 * tl + 4 * grp + i;
-        ok[tl * 4 + i] = (key >= j0) && (key <= t);
+        ok[tl * 4 + i] = (key >= j0) && (key < t);
         sv[tl * 4 + i] = S[tl][i] * scale;
         if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
       }
@@ -559,15 +615,31 @@ __global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) sm_o[wave][16 * m + 4 * grp + i] = O[m][i];
   }
+  {  // q . k_t: waves 0 .. DH/64-1 hold the products
+    float dot = q_e * k_e;
+    for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+    if (lane == 0) sm_dot[wave] = dot;
+  }
   __syncthreads();
   if (threadIdx.x < DH) {
     const int e = threadIdx.x;
     float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+    float s_t = 0.f;
+    if (with_new) {
+      for (int w = 0; w < DH / 64; ++w) s_t += sm_dot[w];
+      s_t *= scale;
+      M = fmaxf(M, s_t);
+    }
     float num = 0.f, den = 0.f;
     for (int w = 0; w < 4; ++w) {
       const float f = __expf(sm_m[w] - M);
       num += f * sm_o[w][e];
       den += f * sm_l[w];
+    }
+    if (with_new) {
+      const float f = __expf(s_t - M);
+      num += f * v_e;
+      den += f;
     }
     if (a.splits == 1) {
       const float r = den > 0.f ? num / den : 0.f;
@@ -576,6 +648,12 @@ __global__ __launch_bounds__(256) void k_attention(AttnArgs a) {
       float *pp = a.part + ((long)blockIdx.y * gridDim.x + (long)b * H + h) * (DH + 2);
       pp[e] = num;
       if (e == 0) { pp[DH] = M; pp[DH + 1] = den; }
+    }
+    if (with_new) {
+      bf16_t *pg = a.pool + (long)page_t * a.kv.page_elems;
+      const int tt = t % a.kv.page_tokens;
+      pg[kv_k_off(h, tt, e, a.kv)] = k_bits;
+      pg[kv_v_off(h, tt, e, a.kv)] = v_bits;
     }
   }
 }

@@ -79,6 +79,7 @@ struct skd_state {
   void *o = nullptr;               // attention output
   void *u = nullptr;               // FFN hidden
   float *partial = nullptr;        // bf16: split-K partials
+  bf16_t *kv_new = nullptr;        // bf16: k and v of the column being processed, [B][k | v][d]
   float *attn_part = nullptr;      // bf16: split-KV partials; fp32: score scratch
   float *logits_dev = nullptr;     // [B][V] (fp32 path always; bf16 path when asked)
   float *pmax = nullptr;
@@ -372,13 +373,13 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       const LayerW &w = st->lw[l];
       GemmArgs ga{};
       ga.B = B; ga.B_pad = st->B_pad; ga.kv = st->geom; ga.t = t; ga.d = d;
-      // q, k, v projection; k and v go straight into this layer's page slot for column t
+      // q, k, v projection; the attention kernel files k and v into this layer's page slot for column t
       ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
-      ga.q_out = q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
+      ga.q_out = q; ga.kv_new = st->kv_new;
       { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U, st->p_qkv.waves); }
       if (grc < 0) return SKD_ERR_SHAPE;
       AttnArgs aa{};
-      aa.q = q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->ragged ? st->order_dev : nullptr;
+      aa.q = q; aa.kv_new = st->kv_new; aa.pool = (bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->ragged ? st->order_dev : nullptr;
       aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
@@ -515,6 +516,7 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
     A(&t16, (size_t)Bp * d); st->q = t16;
     A(&t16, (size_t)Bp * d); st->o = t16; if (rc == SKD_OK) rc = hipMemsetAsync(st->o, 0, (size_t)Bp * d * 2, st->stream) == hipSuccess ? SKD_OK : SKD_ERR_HIP;
     A(&t16, (size_t)Bp * f); st->u = t16;
+    A(&st->kv_new, (size_t)B * 2 * d);
     A(&st->partial, (size_t)st->max_split * Bp * d);
     A(&st->attn_part, (size_t)st->attn_splits * B * c.n_heads * (st->dh + 2));
     const int groups = bf16_gemm_groups(V, st->p_head.R);

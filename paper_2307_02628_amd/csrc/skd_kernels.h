@@ -49,7 +49,7 @@ inline long frag_index(long row, long col, long K) {
 
 enum GemmEpilogue {
   EPI_PARTIAL = 0,  // fp32 partial sums [split][B_pad][N], no bias
-  EPI_QKV = 1,      // + bias; q -> row-major bf16, k/v -> KV page slot of position t
+  EPI_QKV = 1,      // + bias; q -> row-major bf16, k/v -> row-major staging rows (filed into the page by bf16_attention)
   EPI_RELU = 2,     // + bias, ReLU -> fragment-major bf16 [B_pad][N]
   EPI_LOGITS = 3,   // optional fp32 logits [B][N] + per-workgroup (max, argmax) partials
   EPI_QKV_ROWS = 4, // batched prompt: + bias; q -> fragment-major [rows][d]; k/v -> KV page slot of (sequence, position)
@@ -71,11 +71,12 @@ struct GemmArgs {
   // outputs (by epilogue)
   float *partial;      // EPI_PARTIAL
   bf16_t *q_out;       // EPI_QKV: [B_pad][d] row-major
-  bf16_t *kv_pool;     // EPI_QKV
-  const int32_t *bt_layer;  // EPI_QKV: [B][max_pages]
-  int t;               // EPI_QKV: position being written
-  int d;               // EPI_QKV: d_model (N = 3d)
-  KvGeom kv;           // EPI_QKV
+  bf16_t *kv_new;      // EPI_QKV: [B][k | v][d] row-major
+  bf16_t *kv_pool;     // EPI_QKV_ROWS
+  const int32_t *bt_layer;  // EPI_QKV_ROWS: [B][max_pages]
+  int t;               // (unused by the kernels; kept for diagnostics)
+  int d;               // EPI_QKV, EPI_QKV_ROWS: d_model (N = 3d)
+  KvGeom kv;           // EPI_QKV_ROWS
   bf16_t *act_out;     // EPI_RELU
   float *logits;       // EPI_LOGITS (nullable)
   float *pmax;         // EPI_LOGITS: [groups][B_pad]
@@ -93,9 +94,12 @@ void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, i
 // x[b][:] += bias + sum_s partial[s][b][:]; a_out = LayerNorm(x; g, b) fragment-major bf16
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d);
+// Decode attention at position t.  Keys start[b] .. t-1 come from the pages; k and v of position t itself come
+// from kv_new (written by the EPI_QKV projection) and are stored into the page slot of t by this kernel.
 struct AttnArgs {
   const bf16_t *q;          // [B_pad][d] row-major
-  const bf16_t *pool;
+  const bf16_t *kv_new;     // [B][k | v][d] row-major
+  bf16_t *pool;
   const int32_t *bt_layer;  // [B][max_pages]
   const int32_t *start;     // [B] first real column of each row
   const int32_t *order;     // [B] rows sorted by descending length: workgroup x/H handles row order[x/H] (null = identity)
