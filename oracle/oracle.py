@@ -62,6 +62,7 @@ def _lib(real: str) -> C.CDLL:
         lib.ora_free.restype = None
         lib.ora_kv_len.argtypes = [C.c_void_p, C.c_int32]
         lib.ora_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.ora_kv_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         lib.ora_seek.argtypes = [C.c_void_p, C.c_int32]
         lib.ora_seek_ragged.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         lib.ora_column.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
@@ -172,6 +173,15 @@ class Decoder:
 
     def kv_len(self, layer: int) -> int:
         return _check(self._lib.ora_kv_len(self._h, layer), "kv_len")
+
+    def kv_read(self, layer: int, b: int):
+        """Keys and values layer `layer` holds for row b: two [len][d] float64 arrays."""
+        n = self.kv_len(layer)
+        K = np.zeros((n, self.shape.d), dtype=np.float64)
+        V = np.zeros((n, self.shape.d), dtype=np.float64)
+        got = _check(self._lib.ora_kv_read(self._h, layer, b, K.ctypes.data, V.ctypes.data), "kv_read")
+        assert got == n
+        return K, V
 
     def kv_load(self, layer: int, K: np.ndarray, V: np.ndarray):
         K, V = _f32(K), _f32(V)

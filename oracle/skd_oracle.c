@@ -285,6 +285,21 @@ int ora_kv_load(ora_state *st, int32_t l, int32_t cols, const float *Kin, const 
   return ORA_OK;
 }
 
+/* Test hook: copy the keys and values layer l holds for row b ([len][d] double
+ * each) out of the cache.  Returns the number of columns copied. */
+int ora_kv_read(const ora_state *st, int32_t l, int32_t b, double *Kout, double *Vout) {
+  if (!st || !Kout || !Vout) return ORA_ERR_NULL;
+  if (l < 0 || l >= st->s.L || b < 0 || b >= st->B) return ORA_ERR_RANGE;
+  int d = st->s.d, len = st->len[l];
+  if (!st->K[l]) return 0;
+  for (int j = 0; j < len; ++j)
+    for (int e = 0; e < d; ++e) {
+      Kout[(size_t)j * d + e] = (double)st->K[l][((size_t)b * st->N + j) * d + e];
+      Vout[(size_t)j * d + e] = (double)st->V[l][((size_t)b * st->N + j) * d + e];
+    }
+  return len;
+}
+
 /* Companion of ora_kv_load: declare columns 0..cols-1 real for every row and
  * move the column cursor there. */
 int ora_seek(ora_state *st, int32_t cols) {

@@ -327,6 +327,47 @@ def test_rewind_regenerates_identically():
         assert [dec.kv_len(l) for l in range(4)] == lens
 
 
+@pytest.mark.parametrize("shape,batched", [(MID, "1"), (MID, "0"), (MID64, "0")])
+def test_kv_page_contents_match_oracle(shape, batched):
+    # every key and value the cache holds after prefill + decode against the oracle's cache, element by element:
+    # covers the page addressing, the 32-key block boundaries (columns 32, 64, 96), page boundaries (page = 32
+    # tokens here) and the rule that a layer holds exactly the columns at which it ran (Section 2.2)
+    import os
+    w = bf16_weights(shape, 6)
+    B, P, N = 3, 20, 100
+    pr = S.make_prompts(B, P, shape.V, 7)
+    mask = S.make_ragged_mask(B, P, 3, 20, seed=8)
+    mask[1] = 1
+    tape = S.make_token_tape(B, N - P, shape.V, 9)
+    n_min, n_max = 1, shape.L
+    odec = O.Decoder(shape, w, B, N)
+    for i in range(P):
+        odec.column(i, pr[:, i], list(range(shape.L)), mask[:, i], want_logits=False)
+    os.environ["SKD_PREFILL_BATCHED"] = batched
+    try:
+        cfg = skd.make_config(shape, B, P, N, n_min, n_max, page_tokens=32)
+        with skd.Decoder(cfg, w) as dec:
+            dec.prefill(pr, mask)
+            for k in range(N - P):
+                t = P + k
+                odec.column(t, tape[k], O.active_layers(t, P, N, n_min, n_max, 0, shape.L), want_logits=False)
+                dec.decode_step(t, tape[k])
+            start = (mask == 0).sum(axis=1)
+            for l in range(shape.L):
+                assert dec.kv_len(l) == odec.kv_len(l)
+                for b in range(B):
+                    K, V = dec.kv_read(l, b)
+                    Ko, Vo = odec.kv_read(l, b)
+                    assert K.shape == Ko.shape and K.shape[0] == dec.kv_len(l)
+                    sl = slice(int(start[b]), None)      # padded columns are never read: not compared
+                    scale = max(np.abs(Ko[sl]).max(), np.abs(Vo[sl]).max())
+                    assert np.abs(K[sl] - Ko[sl]).max() <= 2e-2 * scale, (l, b)
+                    assert np.abs(V[sl] - Vo[sl]).max() <= 2e-2 * scale, (l, b)
+    finally:
+        os.environ.pop("SKD_PREFILL_BATCHED", None)
+        odec.close()
+
+
 def test_batched_prefill_matches_column_prefill():
     # the whole-prompt path (row-chunked projections + causal prompt attention) against the column-by-column path:
     # same cache contents up to bf16 rounding of differently ordered sums, same logits within the parity tolerance
