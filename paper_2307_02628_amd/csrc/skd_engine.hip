@@ -372,7 +372,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       const int l = layers[i];
       const LayerW &w = st->lw[l];
       GemmArgs ga{};
-      ga.B = B; ga.B_pad = st->B_pad; ga.kv = st->geom; ga.t = t; ga.d = d;
+      ga.B = B; ga.B_pad = st->B_pad; ga.kv = st->geom; ga.d = d;
       // q, k, v projection; the attention kernel files k and v into this layer's page slot for column t
       ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
       ga.q_out = q; ga.kv_new = st->kv_new;

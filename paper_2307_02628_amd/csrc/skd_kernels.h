@@ -43,9 +43,8 @@ int sample_top_p(hipStream_t s, const float *logits, int B, int V, float tempera
 // groups of G (1..4, chosen per matrix as the tile rows one workgroup owns) and
 // stored [tile / G][col / 32][tile % G], so that the G fragments a wave needs for
 // one k-step are G KiB of consecutive addresses.  Activations use G = 1.
-inline long frag_index(long row, long col, long K) {
-  return (((row / 16) * (K / 32) + col / 32) * 64 + (row % 16) + 16 * ((col % 32) / 8)) * 8 + col % 8;
-}
+// Element (row, col) of a G = 1 matrix sits at
+//   (((row / 16) * (K / 32) + col / 32) * 64 + row % 16 + 16 * ((col % 32) / 8)) * 8 + col % 8.
 
 enum GemmEpilogue {
   EPI_PARTIAL = 0,  // fp32 partial sums [split][B_pad][N], no bias
@@ -74,7 +73,6 @@ struct GemmArgs {
   bf16_t *kv_new;      // EPI_QKV: [B][k | v][d] row-major
   bf16_t *kv_pool;     // EPI_QKV_ROWS
   const int32_t *bt_layer;  // EPI_QKV_ROWS: [B][max_pages]
-  int t;               // (unused by the kernels; kept for diagnostics)
   int d;               // EPI_QKV, EPI_QKV_ROWS: d_model (N = 3d)
   KvGeom kv;           // EPI_QKV_ROWS
   bf16_t *act_out;     // EPI_RELU
@@ -82,7 +80,7 @@ struct GemmArgs {
   float *pmax;         // EPI_LOGITS: [groups][B_pad]
   int32_t *pidx;       // EPI_LOGITS
 };
-// R in {1,2,4}: 16-row weight tiles per wave; U in {1,2,4}: k-steps per register buffer (prefetch depth);
+// R in 1..4: 16-row weight tiles per workgroup (each wave accumulates all of them over its share of K); U in {1,2,4}: k-steps per register buffer (prefetch depth);
 // waves in {4,8}: waves per workgroup.  K/32 must be a multiple of a.split.
 // Returns the number of row groups launched (grid.x), or -1 for an unsupported shape.
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U, int waves);
@@ -103,7 +101,7 @@ struct AttnArgs {
   const int32_t *bt_layer;  // [B][max_pages]
   const int32_t *start;     // [B] first real column of each row
   const int32_t *order;     // [B] rows sorted by descending length: workgroup x/H handles row order[x/H] (null = identity)
-  int t;                    // keys start[b] .. t
+  int t;                    // position being processed: cached keys start[b] .. t-1, plus t itself from kv_new
   int B, splits;
   KvGeom kv;
   bf16_t *o;                // fragment-major [B_pad][d]
