@@ -400,6 +400,133 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
   return groups;
 }
 
+// ------------------------------------------------------------------ tiled GEMM for the batched prompt
+// With thousands of activation rows the projections are compute-bound, and the
+// skinny kernel above (every wave fetching its own operands) is limited by
+// L2-to-CU traffic.  Here a workgroup of 8 waves owns a 256 x 256 output tile
+// (16 weight tiles x 16 activation-row tiles); operand fragments of two k-steps
+// (64 KiB) are staged in LDS, double-buffered, and each wave accumulates a
+// 64 x 128 sub-tile (4 x 8 MFMA tiles, 128 accumulator registers), reading 12
+// fragments from LDS per 32 MFMAs.  Fragment-major operands make every global
+// load, LDS store and LDS read a contiguous 1 KiB per wave.
+constexpr int TILE_KC = 2;   // k-steps per stage
+constexpr int TILE_FR = 32;  // fragments per k-step: 16 weight tiles, then 16 activation-row tiles
+
+template <int EPI>
+__global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
+  extern __shared__ bf16x8 tile_lds[];  // [2 stages][TILE_KC][TILE_FR][64 lanes]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wr = wave >> 1, wc = wave & 1;  // sub-tile: weight tiles 4wr .. 4wr+3, activation tiles 8wc .. 8wc+7
+  const int Kf = a.K >> 5, nst = Kf / TILE_KC;
+
+  // workgroup -> output tile.  Workgroups are dealt to the 8 XCDs round-robin; the ones that share an XCD (and
+  // its L2) at any moment should share operands, so each XCD walks its own contiguous range of tiles in blocks
+  // of 4 activation tiles x all weight tiles, weight tile fastest in groups of 4 rows.
+  int tn = blockIdx.x, tm = blockIdx.y;
+  {
+    const int gx = gridDim.x, gy = gridDim.y, total = gx * gy;
+    if ((total & 7) == 0 && (gy & 3) == 0) {
+      const int id = blockIdx.x + gx * blockIdx.y;
+      const int logical = (id & 7) * (total >> 3) + (id >> 3);
+      const int band = logical / (4 * gx), within = logical - band * 4 * gx;
+      tn = within >> 2;
+      tm = band * 4 + (within & 3);
+    }
+  }
+
+  // this wave's share of a stage's global loads: 8 fragments, all weight or all activation tiles of one k-step
+  const int ld_kk = wave >> 2, ld_is_a = (wave >> 1) & 1, ld_t0 = (wave & 1) * 8;
+  const bf16x8 *src[8];
+  long sstride;
+  if (!ld_is_a) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int T = tn * 16 + ld_t0 + i;
+      src[i] = (const bf16x8 *)a.W + (((long)(T / a.G) * Kf + ld_kk) * a.G + T % a.G) * 64 + lane;
+    }
+    sstride = (long)TILE_KC * a.G * 64;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf + ld_kk) * 64 + lane;
+    sstride = (long)TILE_KC * 64;
+  }
+  const int dst0 = (ld_kk * TILE_FR + ld_is_a * 16 + ld_t0) * 64 + lane;  // + i * 64, + stage * TILE_KC * TILE_FR * 64
+
+  floatx4 acc[4][8];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int m = 0; m < 8; ++m) acc[r][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  bf16x8 stg[8];
+  auto gload = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) stg[i] = src[i][(long)st * sstride];
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) tile_lds[buf * (TILE_KC * TILE_FR * 64) + dst0 + i * 64] = stg[i];
+  };
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int kk = 0; kk < TILE_KC; ++kk) {
+      const bf16x8 *base = tile_lds + (buf * TILE_KC + kk) * (TILE_FR * 64) + lane;
+      bf16x8 wf[4], xf[8];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) wf[r] = base[(wr * 4 + r) * 64];
+#pragma unroll
+      for (int m = 0; m < 8; ++m) xf[m] = base[(16 + wc * 8 + m) * 64];
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int m = 0; m < 8; ++m) acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[r], xf[m], acc[r][m], 0, 0, 0);
+    }
+  };
+
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  for (int st = 0; st < nst; ++st) {
+    if (st + 1 < nst) gload(st + 1);   // in flight while this stage is multiplied
+    compute(st & 1);
+    if (st + 1 < nst) lstore((st + 1) & 1);  // that buffer was last read in the previous iteration, before its barrier
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int n0 = ((tn * 16 + wr * 4 + r) << 4) + 4 * (lane >> 4);
+    EpiPre pre[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) pre[m] = epi_prefetch<EPI>(a, ((tm * 16 + wc * 8 + m) << 4) + (lane & 15), n0);
+#pragma unroll
+    for (int m = 0; m < 8; ++m) gemm_epilogue<EPI>(a, ((tm * 16 + wc * 8 + m) << 4) + (lane & 15), n0, acc[r][m], pre[m]);
+  }
+}
+
+// Batched-prompt projections on 256 x 256 tiles.  Returns 0, or -1 when the shape does not tile (the caller then
+// uses bf16_gemm on row chunks).
+int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epi) {
+  if (a.rows <= 0 || a.rows % 256 || a.N % 256 || a.K % (32 * TILE_KC) || a.G < 1 || a.G > 4) return -1;
+  const dim3 grid(a.N / 256, a.rows / 256), blk(512);
+  const size_t lds = (size_t)2 * TILE_KC * TILE_FR * 64 * sizeof(bf16x8);  // 128 KiB of the CU's 160
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void *)k_gemm_tile<EPI_QKV_ROWS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_gemm_tile<EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_gemm_tile<EPI_RELU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return -1;
+    configured = true;
+  }
+  switch (epi) {
+    case EPI_QKV_ROWS: hipLaunchKernelGGL(k_gemm_tile<EPI_QKV_ROWS>, grid, blk, lds, s, a); break;
+    case EPI_RESID: hipLaunchKernelGGL(k_gemm_tile<EPI_RESID>, grid, blk, lds, s, a); break;
+    case EPI_RELU: hipLaunchKernelGGL(k_gemm_tile<EPI_RELU>, grid, blk, lds, s, a); break;
+    default: return -1;
+  }
+  return 0;
+}
+
 // ------------------------------------------------------------------ row kernels: embedding / split-K reduce, + LayerNorm
 // One 1024-thread workgroup per batch row.  These kernels move < 5 MB and are
 // pure latency chains, so each thread keeps its share of the row in registers

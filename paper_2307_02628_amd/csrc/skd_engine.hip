@@ -581,7 +581,7 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
   const skd_config &c = st->cfg;
   const int B = c.batch, P = c.prompt_size, d = c.d_model, f = c.ffn, L = c.L;
   const int P_pad = (P + 15) / 16 * 16;
-  const long rows = (long)B * P_pad, rows_pad = (rows + 127) / 128 * 128;
+  const long rows = (long)B * P_pad, rows_pad = (rows + 255) / 256 * 256;
   hipStream_t s = st->stream;
   if (!st->pf_x) {
     SKDCHECK(dev_alloc(st, &st->pf_x, (size_t)rows_pad * d));
@@ -597,24 +597,30 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
   HIPCHECK(hipMemsetAsync(st->pf_o, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
   bf16_embed_ln_rows(s, cols, st->start_dev, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, st->lw[0].ln1_g,
                      st->lw[0].ln1_b, st->pf_x, st->pf_a, B, P, P_pad, d, c.vocab);
+  // 256 x 256 tiles where the shape allows, else 128-row chunks through the skinny kernel
+  static const int use_tiles = env_int("SKD_PREFILL_TILES", 1);
+  auto proj = [&](const GemmArgs &g, int epi) {
+    if (use_tiles && bf16_gemm_tile(s, g, epi) == 0) return 0;
+    return bf16_gemm(s, g, epi, g.N % 64 ? 1 : 4, 1, 4);
+  };
   for (int l = 0; l < L; ++l) {
     const LayerW &w = st->lw[l];
     GemmArgs ga{};
     ga.B = B; ga.B_pad = 128; ga.rows = (int)rows_pad; ga.P_pad = P_pad; ga.P = P; ga.kv = st->geom; ga.d = d; ga.split = 1;
     ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = st->pf_a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d;
     ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
-    if (bf16_gemm(s, ga, EPI_QKV_ROWS, 3 * d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    if (proj(ga, EPI_QKV_ROWS) < 0) return SKD_ERR_SHAPE;
     AttnRowsArgs aa{};
     aa.q = st->pf_q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
     aa.B = B; aa.P_pad = P_pad; aa.P = P; aa.kv = st->geom; aa.o = st->pf_o;
     bf16_attention_rows(s, aa);
     ga.W = (const bf16_t *)w.wo; ga.G = st->p_out.R; ga.A = st->pf_o; ga.bias = w.bo; ga.N = d; ga.K = d; ga.x = st->pf_x;
-    if (bf16_gemm(s, ga, EPI_RESID, d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    if (proj(ga, EPI_RESID) < 0) return SKD_ERR_SHAPE;
     bf16_ln_rows(s, st->pf_x, w.ln2_g, w.ln2_b, st->pf_a, (int)rows, d);
     ga.W = (const bf16_t *)w.w1; ga.G = st->p_ffn1.R; ga.A = st->pf_a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.act_out = st->pf_u;
-    if (bf16_gemm(s, ga, EPI_RELU, f % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    if (proj(ga, EPI_RELU) < 0) return SKD_ERR_SHAPE;
     ga.W = (const bf16_t *)w.w2; ga.G = st->p_ffn2.R; ga.A = st->pf_u; ga.bias = w.b2; ga.N = d; ga.K = f; ga.x = st->pf_x;
-    if (bf16_gemm(s, ga, EPI_RESID, d % 64 ? 1 : 4, 1, 4) < 0) return SKD_ERR_SHAPE;
+    if (proj(ga, EPI_RESID) < 0) return SKD_ERR_SHAPE;
     if (l + 1 < L) bf16_ln_rows(s, st->pf_x, st->lw[l + 1].ln1_g, st->lw[l + 1].ln1_b, st->pf_a, (int)rows, d);
     st->kv_len[l] = P;
   }

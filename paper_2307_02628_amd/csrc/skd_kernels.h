@@ -85,6 +85,9 @@ struct GemmArgs {
 // Returns the number of row groups launched (grid.x), or -1 for an unsupported shape.
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U, int waves);
 int bf16_gemm_groups(int N, int R);
+// Batched prompt only (a.rows > 0; EPI_QKV_ROWS, EPI_RESID or EPI_RELU): 256 x 256 output tiles with LDS-staged
+// operands.  Needs rows % 256 == 0, N % 256 == 0, K % 64 == 0; returns -1 otherwise (nothing launched).
+int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epilogue);
 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
                    const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
