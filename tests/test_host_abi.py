@@ -86,6 +86,10 @@ def test_error_codes():
         skd.Config(4, 256, 4, 64, 10, 32, 1, 4, 8, 1, 2, 0, 48, skd.FP32, 0),   # page_tokens % 32
         skd.Config(4, 256, 8, 64, 10, 32, 1, 4, 8, 1, 2, 0, 0, skd.BF16, 0),    # bf16 path: head_dim 32
         skd.Config(4, 256, 4, 64, 10, 32, 1, 4, 8, 1, 2, 0, 0, 7, 0),           # unknown dtype
+        skd.Config(4, 256, 4, 64, 10, 32, 129, 4, 8, 1, 2, 0, 0, skd.BF16, 0),  # bf16 path: batch above 128
+        skd.Config(4, 256, 4, 80, 10, 32, 1, 4, 8, 1, 2, 0, 0, skd.BF16, 0),    # bf16 path: FFN width % 32
+        skd.Config(4, 32768, 256, 64, 10, 32, 1, 4, 8, 1, 2, 0, 0, skd.BF16, 0),  # bf16 path: d_model above 16384
+        skd.Config(4, 256, 4, 64, 10, 32, 1, 4, 8, 1, 2, 0, 0, skd.FP32, 2),    # io_on_device is 0 or 1
     ]
     for cfg in bad:
         assert lib.skd_create(C.byref(cfg), C.byref(w), None, C.byref(h)) == skd.ERR_SHAPE
