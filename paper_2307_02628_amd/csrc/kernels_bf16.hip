@@ -8,8 +8,9 @@
 // v_mfma_f32_16x16x32_bf16 (no LDS round trip for streamed data):
 //   * weights are stored "fragment-major" (see skd_kernels.h) so one
 //     wave-wide load = one 16x32 MFMA A-operand;
-//   * activations use the same layout with batch rows in place of weight rows
-//     (B-operand);
+//   * activations are kept in 16-row x 32-column tiles, row-major inside the
+//     tile: one tile is one 1 KiB B-operand load, and a producer that owns a
+//     row stores whole 32-byte sectors;
 //   * K is stored per 16-key tile as A-operand fragments (keys x head_dim),
 //     V per 32-key block as A-operand fragments of V^T (head_dim x keys) with
 //     the key order inside a block chosen so that the softmax weights leave
@@ -44,9 +45,14 @@ __device__ inline float block_sum_f(float v, float *sh) {
   return r;
 }
 
-__device__ inline long d_frag_index(long row, long col, long K) {
-  return (((row >> 4) * (K >> 5) + (col >> 5)) * 64 + (row & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7);
+// Activations [rows][K]: 16-row x 32-column tiles in the order [row / 16][col / 32], each tile 16 rows of 64
+// contiguous bytes.  A producer that owns one row writes 64-byte runs (whole 32-byte sectors); a consumer reads a
+// tile as one MFMA B-operand fragment, lane l taking the 16 bytes at row l % 16, columns 8 * (l / 16) .. + 7,
+// i.e. 16-byte slot act_lane(l) of the 1 KiB tile.
+__device__ inline long d_act_index(long row, long col, long K) {
+  return ((row >> 4) * (K >> 5) + (col >> 5)) * 512 + (row & 15) * 32 + (col & 31);
 }
+__device__ inline int act_lane(int lane) { return (lane & 15) * 4 + (lane >> 4); }
 
 // ------------------------------------------------------------------ KV page addressing
 // Page (one batch row, one layer): [head][32-key block][K block | V block],
@@ -130,7 +136,7 @@ __device__ inline void gemm_epilogue<EPI_RELU>(const GemmArgs &a, int b, int n0,
   if (n0 >= a.N) return;
   for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i] + pre.bias[i], 0.f);
   uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
-  *(uint2 *)&a.act_out[d_frag_index(b, n0, a.N)] = pk;
+  *(uint2 *)&a.act_out[d_act_index(b, n0, a.N)] = pk;
 }
 
 // tile rows that fit the 64 KiB cross-wave reduction buffer at once (each tile row = WAVES * MB KiB)
@@ -148,7 +154,7 @@ __device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, i
   const int which = n0 / a.d, within = n0 - which * a.d;
   const uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
   if (which == 0) {
-    *(uint2 *)&a.q_out[d_frag_index(row, within, a.d)] = pk;
+    *(uint2 *)&a.q_out[d_act_index(row, within, a.d)] = pk;
     return;
   }
   const int h = within / a.kv.dh, e = within - h * a.kv.dh;
@@ -188,7 +194,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
     woff[r] = (((long)(T / a.G) * Kf + kw0) * a.G + T % a.G) * 64;
   }
   const int row0 = blockIdx.z * (MB * 16);  // chunk of activation rows (0 when decoding)
-  const bf16x8 *Ab = (const bf16x8 *)a.A + ((long)blockIdx.z * MB * Kf + kw0) * 64 + lane;
+  const bf16x8 *Ab = (const bf16x8 *)a.A + ((long)blockIdx.z * MB * Kf + kw0) * 64 + act_lane(lane);
 
   floatx4 acc[R][MB];
 #pragma unroll
@@ -407,7 +413,7 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
 // (16 weight tiles x 16 activation-row tiles); operand fragments of two k-steps
 // (64 KiB) are staged in LDS, double-buffered, and each wave accumulates a
 // 64 x 128 sub-tile (4 x 8 MFMA tiles, 128 accumulator registers), reading 12
-// fragments from LDS per 32 MFMAs.  Fragment-major operands make every global
+// fragments from LDS per 32 MFMAs.  Tiled operands make every global
 // load, LDS store and LDS read a contiguous 1 KiB per wave.
 constexpr int TILE_KC = 2;   // k-steps per stage
 constexpr int TILE_FR = 32;  // fragments per k-step: 16 weight tiles, then 16 activation-row tiles
@@ -447,7 +453,8 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     sstride = (long)TILE_KC * a.G * 64;
   } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf + ld_kk) * 64 + lane;
+    for (int i = 0; i < 8; ++i)  // fetched in MFMA lane order, so that LDS holds ready-made fragments
+      src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf + ld_kk) * 64 + act_lane(lane);
     sstride = (long)TILE_KC * 64;
   }
   const int dst0 = (ld_kk * TILE_FR + ld_is_a * 16 + ld_t0) * 64 + lane;  // + i * 64, + stage * TILE_KC * TILE_FR * 64
@@ -534,7 +541,7 @@ int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epi) {
 // every global load it will ever need up front, and the row never touches LDS.
 constexpr int LN_NC = 4;
 
-// v[i] = elements 4c .. 4c+3 of row b.  LayerNorm (mean, biased variance, eps 1e-5) -> bf16 fragment-major row.
+// v[i] = elements 4c .. 4c+3 of row b.  LayerNorm (mean, biased variance, eps 1e-5) -> bf16 row of the activation tiles.
 __device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&gv)[LN_NC], const floatx4 (&bv)[LN_NC],
                                      int d, int b, bf16_t *a_out, float *sh) {
   const int d4 = d >> 2;
@@ -556,7 +563,7 @@ __device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&
     const int c = (int)threadIdx.x + 1024 * i;
     if (c < d4) {
       const floatx4 y = (v[i] - mean) * rstd * gv[i] + bv[i];
-      *(uint2 *)&a_out[d_frag_index(b, 4 * c, d)] = make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
+      *(uint2 *)&a_out[d_act_index(b, 4 * c, d)] = make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
     }
   }
 }
@@ -771,7 +778,7 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
     }
     if (a.splits == 1) {
       const float r = den > 0.f ? num / den : 0.f;
-      a.o[d_frag_index(b, h * DH + e, d)] = (bf16_t)f2bf(r);
+      a.o[d_act_index(b, h * DH + e, d)] = (bf16_t)f2bf(r);
     } else {
       float *pp = a.part + ((long)blockIdx.y * gridDim.x + (long)b * H + h) * (DH + 2);
       pp[e] = num;
@@ -798,7 +805,7 @@ __global__ void k_attn_merge(AttnArgs a) {
     num += f * pp[e];
     den += f * pp[DH + 1];
   }
-  a.o[d_frag_index(b, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
+  a.o[d_act_index(b, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
 }
 
 void bf16_attention(hipStream_t s, const AttnArgs &a) {
@@ -838,7 +845,7 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   bf16x8 qf[QC];
 #pragma unroll
   for (int c = 0; c < QC; ++c)
-    qf[c] = ((const bf16x8 *)a.q)[((row0 >> 4) * (d >> 5) + ((h * DH) >> 5) + c) * 64 + lane];
+    qf[c] = ((const bf16x8 *)a.q)[((row0 >> 4) * (d >> 5) + ((h * DH) >> 5) + c) * 64 + act_lane(lane)];
 
   floatx4 O[VM];
 #pragma unroll
@@ -915,7 +922,7 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
       num += f * sm_o[w][e][c];
       den += f * sm_l[w][c];
     }
-    a.o[d_frag_index(row0 + c, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
+    a.o[d_act_index(row0 + c, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
   }
 }
 

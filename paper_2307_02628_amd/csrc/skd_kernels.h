@@ -34,31 +34,31 @@ int sample_top_p(hipStream_t s, const float *logits, int B, int V, float tempera
                  int32_t *tokens);
 
 // ---------------------------------------------------------------- bf16 production path
-// "Fragment-major" layout of a [rows][K] bf16 matrix (weights: rows = output
-// features; activations: rows = batch rows padded to 16): 16-row x 32-column
-// fragments stored as 64 lanes x 8 elements, lane = (row % 16) + 16 * ((col % 32) / 8),
-// element = col % 8, fragments ordered [row / 16][col / 32].  One fragment is
-// exactly what one lane-wide 16-byte load feeds to v_mfma_f32_16x16x32_bf16.
-// Weight matrices refine the fragment order: the 16-row tiles are bundled in
-// groups of G (1..4, chosen per matrix as the tile rows one workgroup owns) and
-// stored [tile / G][col / 32][tile % G], so that the G fragments a wave needs for
-// one k-step are G KiB of consecutive addresses.  Activations use G = 1.
-// Element (row, col) of a G = 1 matrix sits at
-//   (((row / 16) * (K / 32) + col / 32) * 64 + row % 16 + 16 * ((col % 32) / 8)) * 8 + col % 8.
-
+// Weights [N][K] are "fragment-major": 16-row x 32-column fragments stored as
+// 64 lanes x 8 elements, lane = (row % 16) + 16 * ((col % 32) / 8), element =
+// col % 8: one lane-wide 16-byte load is exactly one A operand of
+// v_mfma_f32_16x16x32_bf16.  The 16-row tiles are bundled in groups of G
+// (1..4, chosen per matrix as the tile rows one workgroup owns) and stored
+// [tile / G][col / 32][tile % G], so that the G fragments a wave needs for one
+// k-step are G KiB of consecutive addresses.
+// Activations [rows][K] (rows padded to 16) use the same 16 x 32 tiles in the
+// order [row / 16][col / 32], but row-major inside a tile (16 rows of 64
+// bytes): one tile is still one 1 KiB B-operand load (lane l reads 16-byte
+// slot (l % 16) * 4 + l / 16), while a producer that owns a row stores 64-byte
+// runs instead of scattered 8- or 16-byte pieces.
 enum GemmEpilogue {
   EPI_PARTIAL = 0,  // fp32 partial sums [split][B_pad][N], no bias
   EPI_QKV = 1,      // + bias; q -> row-major bf16, k/v -> row-major staging rows (filed into the page by bf16_attention)
-  EPI_RELU = 2,     // + bias, ReLU -> fragment-major bf16 [B_pad][N]
+  EPI_RELU = 2,     // + bias, ReLU -> activation tiles bf16 [B_pad][N]
   EPI_LOGITS = 3,   // optional fp32 logits [B][N] + per-workgroup (max, argmax) partials
-  EPI_QKV_ROWS = 4, // batched prompt: + bias; q -> fragment-major [rows][d]; k/v -> KV page slot of (sequence, position)
+  EPI_QKV_ROWS = 4, // batched prompt: + bias; q -> activation tiles [rows][d]; k/v -> KV page slot of (sequence, position)
   EPI_RESID = 5     // batched prompt: x[row][n] += value + bias (fp32 residual stream)
 };
 
 struct GemmArgs {
   const bf16_t *W;     // fragment-major [Nt_pad*16][K], tiles in groups of G
   int G;               // tile-group size of W's layout (Nt_pad is a multiple of 12, so of every G)
-  const bf16_t *A;     // fragment-major [B_pad][K]
+  const bf16_t *A;     // activation tiles [B_pad][K]
   const float *bias;   // [N] or null
   int N, K, B, B_pad;
   int split;           // workgroups along K (grid.y)
@@ -92,7 +92,7 @@ int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epilogue);
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
                    const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
                    int V);
-// x[b][:] += bias + sum_s partial[s][b][:]; a_out = LayerNorm(x; g, b) fragment-major bf16
+// x[b][:] += bias + sum_s partial[s][b][:]; a_out = LayerNorm(x; g, b) as bf16 activation tiles
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d);
 // Decode attention at position t.  Keys start[b] .. t-1 come from the pages; k and v of position t itself come
@@ -107,19 +107,19 @@ struct AttnArgs {
   int t;                    // position being processed: cached keys start[b] .. t-1, plus t itself from kv_new
   int B, splits;
   KvGeom kv;
-  bf16_t *o;                // fragment-major [B_pad][d]
+  bf16_t *o;                // activation tiles [B_pad][d]
   float *part;              // splits > 1: [splits][B*H][dh + 2]
 };
 void bf16_attention(hipStream_t s, const AttnArgs &a);
 // Causal attention of a whole prompt: query rows (b, pos), 16 positions per workgroup, keys start[b] .. pos.
 struct AttnRowsArgs {
-  const bf16_t *q;          // fragment-major [rows][d]
+  const bf16_t *q;          // activation tiles [rows][d]
   const bf16_t *pool;
   const int32_t *bt_layer;  // [B][max_pages]
   const int32_t *start;     // [B]
   int B, P_pad, P;
   KvGeom kv;
-  bf16_t *o;                // fragment-major [rows][d]
+  bf16_t *o;                // activation tiles [rows][d]
 };
 void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a);
 // Batched prompt row kernels: rows = B * P_pad, tokens laid out [P][B].
