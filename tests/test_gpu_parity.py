@@ -67,7 +67,7 @@ def test_mid_ragged_left_padded(dtype, tol):
     compare(MID, w, pr, P, N, 1, 3, tol, mask=mask, dtype=dtype, page_tokens=32)
 
 
-@pytest.mark.parametrize("B", [1, 16, 17, 33])
+@pytest.mark.parametrize("B", [1, 16, 17, 33, 64, 100])     # activation tiles 1, 1, 2, 4, 4, 8 (batch padded to 16/32/64/128)
 def test_batch_tiles_bf16(B):
     w = bf16_weights(MID64, 5)
     P, N = 9, 30
