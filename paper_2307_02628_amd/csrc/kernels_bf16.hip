@@ -820,19 +820,20 @@ void bf16_attention(hipStream_t s, const AttnArgs &a) {
 }
 
 // ------------------------------------------------------------------ causal attention over a whole prompt
-// Same structure as k_attention, but the 16 MFMA columns now carry 16 different
-// queries (consecutive positions of one sequence) instead of one replicated
-// query: one workgroup per (row b, head h, 16-position tile).  Softmax state is
-// per column; key blocks are dealt round-robin to the 4 waves and merged at the
-// end.  Keys: start[b] .. own position (causal).
+// Same block arithmetic as k_attention, but the 16 MFMA columns now carry 16
+// different queries (consecutive positions of one sequence) instead of one
+// replicated query.  A workgroup takes 64 consecutive positions of one (row b,
+// head h): each of its 4 waves owns one 16-position tile and walks all key
+// blocks of that tile itself (no merge; softmax state per column), and since
+// the four waves read almost the same keys at almost the same time, most of
+// their K/V loads are served by the CU's L1.  Keys: start[b] .. own position.
 template <int DH>
 __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   constexpr int QC = DH / 32, VM = DH / 16;
-  __shared__ float sm_m[4][16], sm_l[4][16];
-  __shared__ float sm_o[4][DH][17];  // padded: columns of one dh row fall into different banks
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4, col = lane & 15;
   const int H = a.kv.H, b = blockIdx.x / H, h = blockIdx.x % H, d = H * DH;
-  const int p0 = blockIdx.y * 16;                 // first position of the tile
+  const int p0 = (blockIdx.y * 4 + wave) * 16;    // first position of this wave's tile
+  if (p0 >= a.P_pad) return;                      // (no barriers below)
   const long row0 = (long)b * a.P_pad + p0;       // multiple of 16
   const int j0 = a.start[b];
   const int my_pos = p0 + col;                    // this column's query position
@@ -852,7 +853,7 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   for (int m = 0; m < VM; ++m) O[m] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m_run = -1.0e30f, l_run = 0.f;
 
-  for (int blk = blk_lo + wave; blk < blk_hi; blk += 4) {
+  for (int blk = blk_lo; blk < blk_hi; ++blk) {
     const int page = bt_row[blk / bpp];
     const bf16x8 *kp = (const bf16x8 *)(a.pool + (long)page * a.kv.page_elems + (long)h * (a.kv.page_tokens * DH * 2) +
                                         (long)(blk % bpp) * (64 * DH)) + lane;
@@ -907,27 +908,17 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  if (grp == 0) { sm_m[wave][col] = m_run; sm_l[wave][col] = l_run; }
+  // O[m][i] = numerator of query `col`, head-dim element 16m + 4grp + i
+  const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
 #pragma unroll
-  for (int m = 0; m < VM; ++m)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) sm_o[wave][16 * m + 4 * grp + i][col] = O[m][i];
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < DH * 16; idx += 256) {
-    const int e = idx >> 4, c = idx & 15;
-    const float M = fmaxf(fmaxf(sm_m[0][c], sm_m[1][c]), fmaxf(sm_m[2][c], sm_m[3][c]));
-    float num = 0.f, den = 0.f;
-    for (int w = 0; w < 4; ++w) {
-      const float f = __expf(sm_m[w][c] - M);
-      num += f * sm_o[w][e][c];
-      den += f * sm_l[w][c];
-    }
-    a.o[d_act_index(row0 + c, h * DH + e, d)] = (bf16_t)f2bf(den > 0.f ? num / den : 0.f);
+  for (int m = 0; m < VM; ++m) {
+    const uint2 pk = make_uint2(pack2(O[m][0] * inv, O[m][1] * inv), pack2(O[m][2] * inv, O[m][3] * inv));
+    *(uint2 *)&a.o[d_act_index(row0 + col, h * DH + 16 * m + 4 * grp, d)] = pk;
   }
 }
 
 void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a) {
-  const dim3 grid(a.B * a.kv.H, a.P_pad / 16);
+  const dim3 grid(a.B * a.kv.H, (a.P_pad + 63) / 64);
   if (a.kv.dh == 64) hipLaunchKernelGGL(k_attention_rows<64>, grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL(k_attention_rows<128>, grid, dim3(256), 0, s, a);
 }
@@ -976,6 +967,46 @@ __global__ __launch_bounds__(1024) void k_ln_rows(const float *x, const float *g
   ln_finish_row(v, gv, bv, d, row, a_out, sh);
 }
 
+// LayerNorm of 16 consecutive rows (one activation row tile) per workgroup: wave w keeps row 16 * tile + w in
+// registers (rows up to 4096 wide) and needs no barrier for its statistics; the normalised values go through an
+// 8 KiB LDS buffer per 256 columns so that the tile leaves the workgroup as whole, contiguous 8 KiB runs.
+constexpr int LNW_NC = 16;
+__global__ __launch_bounds__(1024) void k_ln_rows16(const float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
+  __shared__ uint2 stage[2][1024];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 16 + wave;
+  const int nc = d >> 8;  // 256-column chunks
+  const floatx4 *xr = (const floatx4 *)x + row * (d >> 2);
+  floatx4 v[LNW_NC];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < LNW_NC; ++i)
+    if (i < nc) {
+      v[i] = xr[lane + 64 * i];
+      s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    }
+  const float mean = wave_sum_f(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < LNW_NC; ++i)
+    if (i < nc) {
+      const floatx4 t = v[i] - mean;
+      q += (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]);
+    }
+  const float rstd = 1.0f / sqrtf(wave_sum_f(q) / d + 1e-5f);
+  uint2 *out = (uint2 *)(a_out + (long)blockIdx.x * 16 * d);  // the row tile: d / 32 tiles of 1 KiB, back to back
+#pragma unroll
+  for (int i = 0; i < LNW_NC; ++i)
+    if (i < nc) {
+      const floatx4 gv = ((const floatx4 *)g)[lane + 64 * i], bv = ((const floatx4 *)bt)[lane + 64 * i];
+      const floatx4 y = (v[i] - mean) * rstd * gv + bv;
+      // columns 256 i + 4 lane .. + 3 of row `wave`: tile lane / 8 of this chunk, byte wave * 64 + (lane % 8) * 8
+      stage[i & 1][(lane >> 3) * 128 + wave * 8 + (lane & 7)] = make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
+      __syncthreads();
+      out[(long)i * 1024 + threadIdx.x] = stage[i & 1][threadIdx.x];
+    }
+}
+
 __global__ void k_gather_rows(const float *x_rows, float *x_out, int P_pad, int pos, int d) {
   const long src = ((long)blockIdx.x * P_pad + pos) * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) x_out[(long)blockIdx.x * d + k] = x_rows[src + k];
@@ -988,6 +1019,10 @@ void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, const int32_t *sta
                      B, P, P_pad, d, V);
 }
 void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b, bf16_t *a_out, int rows, int d) {
+  if (rows % 16 == 0 && d % 256 == 0 && d <= 256 * LNW_NC) {
+    hipLaunchKernelGGL(k_ln_rows16, dim3(rows / 16), dim3(1024), 0, s, x, g, b, a_out, d);
+    return;
+  }
   hipLaunchKernelGGL(k_ln_rows, dim3(rows), dim3(1024), 0, s, x, g, b, a_out, d);
 }
 void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, int B, int P_pad, int pos, int d) {
