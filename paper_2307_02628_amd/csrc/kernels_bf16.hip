@@ -257,67 +257,66 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
 
   // sum the waves' partial tiles in a fixed order (deterministic).  The LDS buffer holds RS of the R tile rows
   // at a time (64 KiB at most), so wide batches reduce in stages.
-  if constexpr (EPI != EPI_LOGITS) {
+  constexpr int NST = (R + RS - 1) / RS;
+  float cand_v[NST * NP];  // LM head: lanes 0..15 keep the best logit of each (tile row, batch row) they reduced
+  int cand_i[NST * NP];
 #pragma unroll
-    for (int r0 = 0; r0 < R; r0 += RS) {
-      if (r0) __syncthreads();  // the previous stage has been consumed
-      if constexpr (!EARLY) fetch_pre(r0);
+  for (int r0 = 0; r0 < R; r0 += RS) {
+    if (r0) __syncthreads();  // the previous stage has been consumed
+    if constexpr (!EARLY) fetch_pre(r0);
 #pragma unroll
-      for (int rr = 0; rr < RS; ++rr)
+    for (int rr = 0; rr < RS; ++rr)
 #pragma unroll
-        for (int m = 0; m < MB; ++m)
-          if (r0 + rr < R) red[(wave * (RS * MB) + rr * MB + m) * 64 + lane] = acc[r0 + rr < R ? r0 + rr : 0][m];
-      __syncthreads();
+      for (int m = 0; m < MB; ++m)
+        if (r0 + rr < R) red[(wave * (RS * MB) + rr * MB + m) * 64 + lane] = acc[r0 + rr < R ? r0 + rr : 0][m];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = wave + i * WAVES;
+      const int r = r0 + p / MB, m = p % MB;
+      if (p < RS * MB && r < R) {
+        floatx4 v = red[p * 64 + lane];
+        for (int w = 1; w < WAVES; ++w) v += red[(w * (RS * MB) + p) * 64 + lane];
+        const int n0 = (blockIdx.x * R + r) * 16 + 4 * (lane >> 4);
+        if constexpr (EPI != EPI_LOGITS) {
+          gemm_epilogue<EPI>(a, row0 + m * 16 + (lane & 15), n0, v, pre[i]);
+        } else {
+          // optional fp32 logits, and the largest of this tile row per batch row (lowest index on ties)
+          const int b = m * 16 + (lane & 15);
+          float best = -3.0e38f;
+          int bi = 0x7fffffff;
+          for (int j = 0; j < 4; ++j) {
+            if (n0 + j < a.N) {
+              if (a.logits && b < a.B) a.logits[(long)b * a.N + n0 + j] = v[j];
+              if (v[j] > best) { best = v[j]; bi = n0 + j; }
+            }
+          }
+          for (int o = 16; o < 64; o <<= 1) {  // across the four 4-row groups of this column
+            const float ov = __shfl_xor(best, o);
+            const int oi = __shfl_xor(bi, o);
+            if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+          }
+          cand_v[(r0 / RS) * NP + i] = best;
+          cand_i[(r0 / RS) * NP + i] = bi;
+        }
+      }
+    }
+  }
+  if constexpr (EPI == EPI_LOGITS) {
+    __syncthreads();  // the reduction buffer is free: it now collects the candidates, [R * MB][16] values and indices
+    float *cv = (float *)red;
+    int *ci = (int *)red + RM * 16;
+#pragma unroll
+    for (int st = 0; st < NST; ++st)
 #pragma unroll
       for (int i = 0; i < NP; ++i) {
         const int p = wave + i * WAVES;
-        const int r = r0 + p / MB, m = p % MB;
-        if (p < RS * MB && r < R) {
-          floatx4 v = red[p * 64 + lane];
-          for (int w = 1; w < WAVES; ++w) v += red[(w * (RS * MB) + p) * 64 + lane];
-          gemm_epilogue<EPI>(a, row0 + m * 16 + (lane & 15), (blockIdx.x * R + r) * 16 + 4 * (lane >> 4), v, pre[i]);
+        const int r = st * RS + p / MB, m = p % MB;
+        if (p < RS * MB && r < R && lane < 16) {
+          cv[(r * MB + m) * 16 + lane] = cand_v[st * NP + i];
+          ci[(r * MB + m) * 16 + lane] = cand_i[st * NP + i];
         }
       }
-    }
-    return;
-  }
-  static_assert(EPI != EPI_LOGITS || RS == R, "the LM-head epilogue reduces in one stage");
-#pragma unroll
-  for (int r = 0; r < R; ++r)
-#pragma unroll
-    for (int m = 0; m < MB; ++m) red[(wave * RM + r * MB + m) * 64 + lane] = acc[r][m];
-  __syncthreads();
-
-  if constexpr (EPI == EPI_LOGITS) {
-    floatx4 v[(RM + WAVES - 1) / WAVES];
-    int np = 0;
-    for (int p = wave; p < RM; p += WAVES, ++np) {
-      v[np] = red[p * 64 + lane];
-      for (int w = 1; w < WAVES; ++w) v[np] += red[(w * RM + p) * 64 + lane];
-    }
-    __syncthreads();  // everyone has read its tiles: the buffer is reused for the argmax candidates
-    float *cv = (float *)red;             // [RM][16]
-    int *ci = (int *)red + RM * 16;       // [RM][16]
-    np = 0;
-    for (int p = wave; p < RM; p += WAVES, ++np) {
-      const int r = p / MB, m = p % MB;
-      const int b = m * 16 + (lane & 15);
-      const int n0 = (blockIdx.x * R + r) * 16 + 4 * (lane >> 4);
-      float best = -3.0e38f;
-      int bi = 0x7fffffff;
-      for (int i = 0; i < 4; ++i) {
-        if (n0 + i < a.N) {
-          if (a.logits && b < a.B) a.logits[(long)b * a.N + n0 + i] = v[np][i];
-          if (v[np][i] > best) { best = v[np][i]; bi = n0 + i; }
-        }
-      }
-      for (int o = 16; o < 64; o <<= 1) {  // across the four 4-row groups of this column
-        const float ov = __shfl_xor(best, o);
-        const int oi = __shfl_xor(bi, o);
-        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
-      }
-      if (lane < 16) { cv[p * 16 + lane] = best; ci[p * 16 + lane] = bi; }
-    }
     __syncthreads();
     if (threadIdx.x < MB * 16) {
       const int m = threadIdx.x >> 4, c = threadIdx.x & 15;
@@ -350,10 +349,7 @@ static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid
     case EPI_RESID:
       if constexpr (MB == 8) hipLaunchKernelGGL((k_gemm<MB, R, EPI_RESID, U, WAVES>), grid, blk, lds, s, a);
       break;
-    default:
-      if constexpr (gemm_stage_rows(WAVES, R, MB) == R)
-        hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a);
-      break;
+    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a); break;
   }
 }
 template <int MB, int R, int U>
@@ -384,9 +380,6 @@ static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int 
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves) {
   const int MB = a.B_pad / 16;
   if (R < 1 || R > 4 || a.G < 1 || a.G > 4 || (waves != 4 && waves != 8) || MB < 1 || MB > 8) return -1;
-  // the LM-head epilogue keeps all tile rows of the workgroup in the 64 KiB reduction buffer (the caller sizes
-  // its argmax partials by R, so R is never changed here)
-  if (epi == EPI_LOGITS && waves * R * MB > 64) return -1;
   const int split = epi == EPI_LOGITS ? 1 : a.split;
   const int Kf = a.K / 32;
   if (Kf % split) return -1;            // equal K ranges per workgroup

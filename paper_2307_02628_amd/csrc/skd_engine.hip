@@ -460,8 +460,6 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
     ov("SKD_U_OUT", st->p_out.U, 1, 4); ov("SKD_U_FFN2", st->p_ffn2.U, 1, 4);
     ov("SKD_W_QKV", st->p_qkv.waves, 4, 8); ov("SKD_W_FFN1", st->p_ffn1.waves, 4, 8); ov("SKD_W_HEAD", st->p_head.waves, 4, 8);
     ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
-    while (st->p_head.R > 1 && st->p_head.waves * st->p_head.R * (Bp / 16) > 64) --st->p_head.R;  // LM-head epilogue: one reduction stage
-    if (st->p_head.waves * st->p_head.R * (Bp / 16) > 64) st->p_head.waves = 4;
   }
 
   // ---- weights
