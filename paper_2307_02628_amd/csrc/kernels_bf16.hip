@@ -82,20 +82,24 @@ __device__ inline long kv_v_off(int h, int tt, int e, const KvGeom &g) {
 // chain of dependent round trips.
 struct EpiPre {
   floatx4 bias, x;
-  int page;
+  int page, slot;
 };
 template <int EPI>
 __device__ inline EpiPre epi_prefetch(const GemmArgs &a, int row, int n0) {
   EpiPre p;
   p.bias = p.x = floatx4{0.f, 0.f, 0.f, 0.f};
   p.page = 0;
+  p.slot = 0;
   if constexpr (EPI == EPI_QKV || EPI == EPI_RELU || EPI == EPI_QKV_ROWS || EPI == EPI_RESID) {
     if (n0 + 3 < a.N) p.bias = *(const floatx4 *)&a.bias[n0];  // N is a multiple of 4 for these
   }
   if constexpr (EPI == EPI_QKV_ROWS) {
     const int b = row / a.P_pad, pos = row - b * a.P_pad;
-    if (n0 >= a.d && n0 < a.N && row < a.rows && b < a.B && pos < a.P)
-      p.page = a.bt_layer[(long)b * a.kv.max_pages + pos / a.kv.page_tokens];
+    if (n0 >= a.d && n0 < a.N && row < a.rows && b < a.B && pos < a.P) {
+      const int slot = pos - a.start[b];  // keys are stored by real position; padding columns store nothing
+      p.page = slot >= 0 ? a.bt_layer[(long)b * a.kv.max_pages + slot / a.kv.page_tokens] : -1;
+      p.slot = slot;
+    }
   }
   if constexpr (EPI == EPI_RESID) {
     if (n0 + 3 < a.N && row < a.rows) p.x = *(const floatx4 *)&a.x[(long)row * a.N + n0];
@@ -157,9 +161,10 @@ __device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, i
     *(uint2 *)&a.q_out[d_act_index(row, within, a.d)] = pk;
     return;
   }
+  if (pre.page < 0) return;  // padding column
   const int h = within / a.kv.dh, e = within - h * a.kv.dh;
   bf16_t *pg = a.kv_pool + (long)pre.page * a.kv.page_elems;
-  const int tt = pos % a.kv.page_tokens;
+  const int tt = pre.slot % a.kv.page_tokens;
   if (which == 1) {
     *(uint2 *)&pg[kv_k_off(h, tt, e, a.kv)] = pk;
   } else {
@@ -640,7 +645,10 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
   // longest rows are dispatched first, so that the last workgroups to start are the short ones
   const int b = a.order ? a.order[blockIdx.x / H] : (int)(blockIdx.x / H);
   const int j0 = a.start[b], t = a.t;
-  const int blk_lo = j0 >> 5, blk_hi = (t + 31) >> 5;  // blocks [blk_lo, blk_hi) hold the cached keys j0 .. t-1
+  // a row's keys are stored by real position: column j sits in slot j - j0, so neither end of the row's first
+  // block is padding.  Slots 0 .. len-1 are cached; slot len (column t) arrives in kv_new.
+  const int len = t - j0;  // cached keys of this row (negative: column t is still padding for it)
+  const int blk_lo = 0, blk_hi = (len + 31) >> 5;
   const int nblk = blk_hi - blk_lo;
   const int per = (nblk + a.splits - 1) / a.splits;
   const int my_lo = blk_lo + (int)blockIdx.y * per;
@@ -659,7 +667,7 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
   // are merged, and is filed into its page slot at the very end: nothing in this kernel reads that slot, and
   // the lines around it have just been read, so the small stores hit lines that are resident in L2 (the same
   // stores from the projection's epilogue or from a later kernel cost about 3 us per layer).
-  const bool with_new = blockIdx.y == gridDim.y - 1 && t >= j0;
+  const bool with_new = blockIdx.y == gridDim.y - 1 && len >= 0;
   float q_e = 0.f, k_e = 0.f, v_e = 0.f;
   bf16_t k_bits = 0, v_bits = 0;
   int page_t = 0;
@@ -670,7 +678,7 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
     q_e = bf2f(a.q[(long)b * d + h * DH + threadIdx.x]);
     k_e = bf2f(k_bits);
     v_e = bf2f(v_bits);
-    page_t = bt_row[t / a.kv.page_tokens];
+    page_t = bt_row[len / a.kv.page_tokens];
   }
 
   floatx4 O[VM];
@@ -706,7 +714,7 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int key = blk * 32 + 16 * tl + 4 * grp + i;
-        ok[tl * 4 + i] = (key >= j0) && (key < t);
+        ok[tl * 4 + i] = key < len;
         sv[tl * 4 + i] = S[tl][i] * scale;
         if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
       }
@@ -779,7 +787,7 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
     }
     if (with_new) {
       bf16_t *pg = a.pool + (long)page_t * a.kv.page_elems;
-      const int tt = t % a.kv.page_tokens;
+      const int tt = len % a.kv.page_tokens;
       pg[kv_k_off(h, tt, e, a.kv)] = k_bits;
       pg[kv_v_off(h, tt, e, a.kv)] = v_bits;
     }
@@ -831,7 +839,8 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   const int j0 = a.start[b];
   const int my_pos = p0 + col;                    // this column's query position
   const int last = min(p0 + 15, a.P - 1);         // last real position of the tile
-  const int blk_lo = j0 >> 5, blk_hi = (last >> 5) + 1;
+  const int my_len = my_pos - j0 + 1;             // keys of this query: slots 0 .. my_len-1 (stored by real position)
+  const int blk_lo = 0, blk_hi = last >= j0 ? ((last - j0) >> 5) + 1 : 0;
   const int bpp = a.kv.page_tokens >> 5;
   const int32_t *bt_row = a.bt_layer + (long)b * a.kv.max_pages;
   const float scale = 1.0f / sqrtf((float)DH);
@@ -872,7 +881,7 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int key = blk * 32 + 16 * tl + 4 * grp + i;
-        ok[tl * 4 + i] = (key >= j0) && (key <= my_pos);
+        ok[tl * 4 + i] = key < my_len;
         sv[tl * 4 + i] = S[tl][i] * scale;
         if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
       }
@@ -1103,34 +1112,41 @@ void prep_to_f32(hipStream_t s, const void *src, int src_is_bf16, float *dst, lo
 }
 
 // ------------------------------------------------------------------ KV debug hooks (bf16 pages)
-__global__ void k_kv_load_bf16(const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer, int cols,
-                               KvGeom g) {
+__global__ void k_kv_load_bf16(const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer,
+                               const int32_t *start, int cols, KvGeom g) {
   const int b = blockIdx.y, j = blockIdx.x, d = g.H * g.dh;
-  const int page = bt_layer[(long)b * g.max_pages + j / g.page_tokens];
+  const int slot = j - start[b];  // stored by real position
+  if (slot < 0) return;
+  const int page = bt_layer[(long)b * g.max_pages + slot / g.page_tokens];
   bf16_t *pg = pool + (long)page * g.page_elems;
-  const int tt = j % g.page_tokens;
+  const int tt = slot % g.page_tokens;
   for (int k = threadIdx.x; k < d; k += blockDim.x) {
     const int h = k / g.dh, e = k % g.dh;
     pg[kv_k_off(h, tt, e, g)] = (bf16_t)f2bf(K ? K[((long)b * cols + j) * d + k] : 0.f);
     pg[kv_v_off(h, tt, e, g)] = (bf16_t)f2bf(V ? V[((long)b * cols + j) * d + k] : 0.f);
   }
 }
-__global__ void k_kv_read_bf16(const bf16_t *pool, const int32_t *bt_row, float *K, float *V, KvGeom g) {
-  const int j = blockIdx.x, d = g.H * g.dh;
-  const bf16_t *pg = pool + (long)bt_row[j / g.page_tokens] * g.page_elems;
-  const int tt = j % g.page_tokens;
+__global__ void k_kv_read_bf16(const bf16_t *pool, const int32_t *bt_row, int start, float *K, float *V, KvGeom g) {
+  const int j = blockIdx.x, d = g.H * g.dh, slot = j - start;
+  if (slot < 0) {  // padding column: nothing is stored for it
+    for (int k = threadIdx.x; k < d; k += blockDim.x) K[(long)j * d + k] = V[(long)j * d + k] = 0.f;
+    return;
+  }
+  const bf16_t *pg = pool + (long)bt_row[slot / g.page_tokens] * g.page_elems;
+  const int tt = slot % g.page_tokens;
   for (int k = threadIdx.x; k < d; k += blockDim.x) {
     const int h = k / g.dh, e = k % g.dh;
     K[(long)j * d + k] = bf2f(pg[kv_k_off(h, tt, e, g)]);
     V[(long)j * d + k] = bf2f(pg[kv_v_off(h, tt, e, g)]);
   }
 }
-void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer, int cols,
-                  int B, KvGeom g) {
-  if (cols > 0) hipLaunchKernelGGL(k_kv_load_bf16, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, cols, g);
+void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer,
+                  const int32_t *start, int cols, int B, KvGeom g) {
+  if (cols > 0) hipLaunchKernelGGL(k_kv_load_bf16, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, start, cols, g);
 }
-void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g) {
-  if (len > 0) hipLaunchKernelGGL(k_kv_read_bf16, dim3(len), dim3(256), 0, s, pool, bt_row, K, V, g);
+void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int start, int len, float *K, float *V,
+                  KvGeom g) {
+  if (len > 0) hipLaunchKernelGGL(k_kv_read_bf16, dim3(len), dim3(256), 0, s, pool, bt_row, start, K, V, g);
 }
 
 }  // namespace skd

@@ -71,6 +71,7 @@ struct skd_state {
   int32_t *order_dev = nullptr;    // [B] rows by descending real length (attention dispatch order)
   bool ragged = false;             // rows differ in length: use order_dev
   int32_t *start_dev = nullptr;    // [B] first real column
+  std::vector<int32_t> start_host;
   int32_t *argmax_dev = nullptr;   // [B]
   float *u_dev = nullptr;          // [B] uniform numbers of the sampling head
   float *x = nullptr;              // residual stream fp32 [B_pad][d]
@@ -566,6 +567,7 @@ static int upload_start(skd_state *st, const std::vector<int32_t> &start) {
   for (int b = 0; b < B; ++b) order[b] = b;
   std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return start[x] < start[y]; });
   st->ragged = *std::max_element(start.begin(), start.end()) != *std::min_element(start.begin(), start.end());
+  st->start_host = start;
   HIPCHECK(hipMemcpyAsync(st->start_dev, start.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
   HIPCHECK(hipMemcpyAsync(st->order_dev, order.data(), B * sizeof(int32_t), hipMemcpyHostToDevice, st->stream));
   HIPCHECK(hipStreamSynchronize(st->stream));
@@ -606,7 +608,7 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
     GemmArgs ga{};
     ga.B = B; ga.B_pad = 128; ga.rows = (int)rows_pad; ga.P_pad = P_pad; ga.P = P; ga.kv = st->geom; ga.d = d; ga.split = 1;
     ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = st->pf_a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d;
-    ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
+    ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l); ga.start = st->start_dev;
     if (proj(ga, EPI_QKV_ROWS) < 0) return SKD_ERR_SHAPE;
     AttnRowsArgs aa{};
     aa.q = st->pf_q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
@@ -851,6 +853,11 @@ extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const
   if (start_in)
     for (int b = 0; b < B; ++b)
       if (start_in[b] < 0 || start_in[b] >= cols) return SKD_ERR_RANGE;
+  {
+    std::vector<int32_t> start(B, 0);
+    if (start_in) start.assign(start_in, start_in + B);
+    SKDCHECK(upload_start(st, start));  // the bf16 pages are addressed by real position
+  }
   const size_t n = (size_t)B * cols * d;
   float *kd = nullptr, *vd = nullptr;
   HIPCHECK(hipMalloc((void **)&kd, n * sizeof(float)));
@@ -869,7 +876,7 @@ extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const
       break;
     }
     if (st->bf16)
-      kv_load_bf16(st->stream, have ? kd : nullptr, have ? vd : nullptr, (bf16_t *)st->pool, bt_layer(st, l), cols, B, st->geom);
+      kv_load_bf16(st->stream, have ? kd : nullptr, have ? vd : nullptr, (bf16_t *)st->pool, bt_layer(st, l), st->start_dev, cols, B, st->geom);
     else
       kv_load_f32(st->stream, have ? kd : nullptr, have ? vd : nullptr, (float *)st->pool, bt_layer(st, l), cols, B, st->geom);
     if (hipStreamSynchronize(st->stream) != hipSuccess) { rc = SKD_ERR_HIP; break; }
@@ -878,9 +885,6 @@ extern "C" int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const
   (void)hipFree(kd);
   (void)hipFree(vd);
   if (rc != SKD_OK) return rc;
-  std::vector<int32_t> start(B, 0);
-  if (start_in) start.assign(start_in, start_in + B);
-  SKDCHECK(upload_start(st, start));
   st->prefilled = true;
   st->steps_done = cols - c.prompt_size;
   st->have_hidden = false;
@@ -898,7 +902,7 @@ extern "C" int skd_debug_kv_read(skd_state *st, int32_t layer, int32_t b, float 
   HIPCHECK(hipMalloc((void **)&kd, (size_t)len * d * sizeof(float)));
   if (hipMalloc((void **)&vd, (size_t)len * d * sizeof(float)) != hipSuccess) { (void)hipFree(kd); return SKD_ERR_NOMEM; }
   const int32_t *row = bt_layer(st, layer) + (size_t)b * st->geom.max_pages;
-  if (st->bf16) kv_read_bf16(st->stream, (const bf16_t *)st->pool, row, len, kd, vd, st->geom);
+  if (st->bf16) kv_read_bf16(st->stream, (const bf16_t *)st->pool, row, st->start_host.empty() ? 0 : st->start_host[b], len, kd, vd, st->geom);
   else kv_read_f32(st->stream, (const float *)st->pool, row, len, kd, vd, st->geom);
   int rc = SKD_OK;
   if (hipMemcpyAsync(k_out, kd, (size_t)len * d * sizeof(float), hipMemcpyDeviceToHost, st->stream) != hipSuccess ||

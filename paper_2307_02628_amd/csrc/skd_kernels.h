@@ -9,7 +9,10 @@ namespace skd {
 typedef uint16_t bf16_t;  // raw bfloat16 bit pattern in host-visible signatures
 
 // Geometry of the paged KV cache.  A page holds `page_tokens` consecutive
-// positions of ONE batch row in ONE layer, all heads.
+// positions of ONE batch row in ONE layer, all heads.  On the bf16 path a row's
+// keys are stored by real position (column j of a row that starts at column
+// start[b] sits in slot j - start[b]; padding columns store nothing), so that a
+// left-padded row reads no padding; the fp32 path stores by column.
 struct KvGeom {
   int page_tokens;
   int max_pages;      // block-table entries per (layer, row)
@@ -73,6 +76,7 @@ struct GemmArgs {
   bf16_t *kv_new;      // EPI_QKV: [B][k | v][d] row-major
   bf16_t *kv_pool;     // EPI_QKV_ROWS
   const int32_t *bt_layer;  // EPI_QKV_ROWS: [B][max_pages]
+  const int32_t *start;     // EPI_QKV_ROWS: [B] first real column of each row (keys are stored by real position)
   int d;               // EPI_QKV, EPI_QKV_ROWS: d_model (N = 3d)
   KvGeom kv;           // EPI_QKV_ROWS
   bf16_t *act_out;     // EPI_RELU
@@ -95,7 +99,7 @@ void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, i
 // x[b][:] += bias + sum_s partial[s][b][:]; a_out = LayerNorm(x; g, b) as bf16 activation tiles
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d);
-// Decode attention at position t.  Keys start[b] .. t-1 come from the pages; k and v of position t itself come
+// Decode attention at position t.  Keys of columns start[b] .. t-1 (slots 0 .. t-start[b]-1) come from the pages; k and v of position t itself come
 // from kv_new (written by the EPI_QKV projection) and are stored into the page slot of t by this kernel.
 struct AttnArgs {
   const bf16_t *q;          // [B_pad][d] row-major
@@ -111,7 +115,7 @@ struct AttnArgs {
   float *part;              // splits > 1: [splits][B*H][dh + 2]
 };
 void bf16_attention(hipStream_t s, const AttnArgs &a);
-// Causal attention of a whole prompt: query rows (b, pos), 16 positions per workgroup, keys start[b] .. pos.
+// Causal attention of a whole prompt: query rows (b, pos), 64 positions per workgroup, keys of columns start[b] .. pos.
 struct AttnRowsArgs {
   const bf16_t *q;          // activation tiles [rows][d]
   const bf16_t *pool;
@@ -140,9 +144,10 @@ void prep_to_f32(hipStream_t s, const void *src, int src_is_bf16, float *dst, lo
 // KV debug hooks: [B][cols][d] fp32 <-> pages
 void kv_load_f32(hipStream_t s, const float *K, const float *V, float *pool, const int32_t *bt_layer, int cols, int B,
                  KvGeom g);
-void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer, int cols,
-                  int B, KvGeom g);
+void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer,
+                  const int32_t *start, int cols, int B, KvGeom g);
 void kv_read_f32(hipStream_t s, const float *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g);
-void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g);
+void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int start, int len, float *K, float *V,
+                  KvGeom g);
 
 }  // namespace skd
