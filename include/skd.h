@@ -223,7 +223,8 @@ int skd_debug_read_hidden(skd_state *st, float *x_out);
  * layer's cache (rounded to the path's KV precision); layers with NULL entries
  * hold zeros.  Layers that leave the active window before column `cols` keep
  * only what they reserved.  start [B] (may be NULL = no padding) gives each
- * row's number of left-padding columns, 0 <= start[b] < cols.  Used to set up
+ * row's number of left-padding columns, 0 <= start[b] < cols; the entries of
+ * Kin / Vin at those columns are ignored.  Used to set up
  * single decode steps at long contexts without running a long prompt.  Kin /
  * Vin are host arrays of L host pointers.  Errors: SKD_ERR_NULL,
  * SKD_ERR_RANGE, SKD_ERR_NOMEM, SKD_ERR_HIP. */
@@ -231,7 +232,9 @@ int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, cons
                       const int32_t *start);
 
 /* Read back row b of layer l's cache: k_out, v_out [len][d] fp32 with
- * len = skd_kv_len(l). */
+ * len = skd_kv_len(l), indexed by column.  Left-padding columns of the row are
+ * never attended to; what is returned for them is unspecified (the bf16 path
+ * stores nothing for them and returns zeros). */
 int skd_debug_kv_read(skd_state *st, int32_t layer, int32_t b, float *k_out, float *v_out);
 
 /* Per-kernel timing.  While enabled, every kernel launch of this state is
