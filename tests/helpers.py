@@ -43,7 +43,7 @@ def rel_err(got, ref):
     return d / rng
 
 
-def check_argmax(got_logits, ref_logits, tol):
+def check_argmax(got_logits, ref_logits, tol, min_decided=0.5):
     """Greedy tokens must agree wherever the oracle's top-1/top-2 margin exceeds twice the logit tolerance."""
     ref = np.asarray(ref_logits)
     got = np.asarray(got_logits)
@@ -51,12 +51,12 @@ def check_argmax(got_logits, ref_logits, tol):
     srt = np.sort(ref, axis=-1)
     margin = srt[..., -1] - srt[..., -2]
     decided = margin > 2 * tol * rng
-    assert decided.mean() > 0.5
+    assert decided.mean() >= min_decided                      # the check must not be vacuous
     np.testing.assert_array_equal(got.argmax(-1)[decided], ref.argmax(-1)[decided])
 
 
 def compare(shape, w, prompts, P, N, n_min, n_max, tol, warmup=0, mask=None, dtype=skd.BF16, page_tokens=0,
-            steps=None, tape=None):
+            steps=None, tape=None, min_decided=0.5):
     ref = O.generate(shape, w, prompts, P, N, n_min, n_max, warmup, mask, tape=tape, steps=steps)
     got = run_hip(shape, w, prompts, P, N, n_min, n_max, warmup, mask, tape=ref["fed"], dtype=dtype,
                   page_tokens=page_tokens, steps=steps)
@@ -64,5 +64,5 @@ def compare(shape, w, prompts, P, N, n_min, n_max, tol, warmup=0, mask=None, dty
     assert got["kv_len"] == ref["kv_len"]                     # a layer stores exactly the columns it ran at
     err = rel_err(got["logits"], ref["logits"])
     assert err.max() <= tol, f"per-step max|dlogit|/range = {err}"
-    check_argmax(got["logits"], ref["logits"], tol)
+    check_argmax(got["logits"], ref["logits"], tol, min_decided)
     return got, ref, err
