@@ -712,7 +712,8 @@ extern "C" int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_i
 }
 
 // Final LayerNorm + LM head (+ greedy argmax into argmax_dev).  logits_target: device buffer [B][V] or null.
-static int head_logits(skd_state *st, float *logits_target) {
+// final LayerNorm output -> logits (optional) and, unless the caller picks the token itself, the greedy token
+static int head_logits(skd_state *st, float *logits_target, bool want_argmax = true) {
   const skd_config &c = st->cfg;
   const int B = c.batch, d = c.d_model, V = c.vocab;
   hipStream_t s = st->stream;
@@ -720,7 +721,7 @@ static int head_logits(skd_state *st, float *logits_target) {
     float *lg = logits_target ? logits_target : st->logits_dev;
     { ProfScope ps_(st, SKD_PROF_OTHER); f32_layernorm(s, st->x, st->lnf_g, st->lnf_b, (float *)st->a, B, d); }
     { ProfScope ps_(st, SKD_PROF_OTHER); f32_linear(s, (const float *)st->head, nullptr, (const float *)st->a, lg, B, d, V, 0, 0); }
-    { ProfScope ps_(st, SKD_PROF_OTHER); f32_argmax(s, lg, st->argmax_dev, B, V); }
+    if (want_argmax) { ProfScope ps_(st, SKD_PROF_OTHER); f32_argmax(s, lg, st->argmax_dev, B, V); }
   } else {
     GemmArgs ga{};
     ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.G = st->p_head.R; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
@@ -728,7 +729,7 @@ static int head_logits(skd_state *st, float *logits_target) {
     int groups = 0;
     { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves); }
     if (groups < 0) return SKD_ERR_SHAPE;
-    { ProfScope ps_(st, SKD_PROF_ARGMAX); bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B); }
+    if (want_argmax) { ProfScope ps_(st, SKD_PROF_ARGMAX); bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B); }
   }
   HIPCHECK(hipGetLastError());
   return SKD_OK;
@@ -774,7 +775,7 @@ extern "C" int skd_logits_sample(skd_state *st, const float *u, float temperatur
     u_dev = st->u_dev;
   }
   float *lg = (logits_out && c.io_on_device) ? logits_out : st->logits_dev;
-  SKDCHECK(head_logits(st, lg));
+  SKDCHECK(head_logits(st, lg, false));
   { ProfScope ps_(st, SKD_PROF_ARGMAX); if (sample_top_p(s, lg, B, V, temperature, top_p, u_dev, st->argmax_dev) < 0) return SKD_ERR_SHAPE; }
   HIPCHECK(hipGetLastError());
   st->have_argmax = true;  // skd_decode_step(.., NULL) continues from the sampled tokens
