@@ -368,6 +368,16 @@ def test_kv_page_contents_match_oracle(shape, batched):
         odec.close()
 
 
+@pytest.mark.parametrize("d", [8192, 16384])
+def test_wide_model_bf16(d):
+    # d_model 8192 and the maximum, 16384: the row kernels (embedding, split-K reduce, LayerNorm) hold two and four
+    # register chunks per thread, the projections run 256 and 512 k-steps, 64 and 128 heads
+    shape = S.ModelShape(L=1, d=d, H=d // 128, f=128, V=100, max_pos=16)
+    w = bf16_weights(shape, 31)
+    pr = S.make_prompts(2, 3, shape.V, 32)
+    compare(shape, w, pr, 3, 6, 1, 1, BF16_TOL, dtype=skd.BF16, min_decided=0.0)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_small_configurations(seed):
     # seeded draw over the knobs that change code paths: head size, batch tile count, prompt length against the
