@@ -368,6 +368,22 @@ def test_kv_page_contents_match_oracle(shape, batched):
         odec.close()
 
 
+def test_vocabulary_above_sampler_limit():
+    # the sampling head keeps a row of probabilities in registers: vocabularies above 65536 are refused with
+    # SKD_ERR_SHAPE, while the LM head and greedy argmax have no such limit
+    shape = S.ModelShape(L=1, d=128, H=2, f=64, V=70001, max_pos=8)
+    w = bf16_weights(shape, 41)
+    pr = S.make_prompts(2, 2, shape.V, 42)
+    cfg = skd.make_config(shape, 2, 2, 4, 1, 1, dtype=skd.BF16)
+    ref = O.generate(shape, w, pr, 2, 4, 1, 1, steps=0)
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr, None)
+        rc, _, _ = dec.logits_sample_rc(np.array([0.5, 0.5], dtype=np.float32), 0.3, 0.7)
+        assert rc == skd.ERR_SHAPE
+        tok, lg = dec.logits_argmax()
+        assert rel_err(lg[None], ref["logits"][:1]).max() <= BF16_TOL
+
+
 @pytest.mark.parametrize("d", [8192, 16384])
 def test_wide_model_bf16(d):
     # d_model 8192 and the maximum, 16384: the row kernels (embedding, split-K reduce, LayerNorm) hold two and four
