@@ -368,6 +368,34 @@ def test_kv_page_contents_match_oracle(shape, batched):
         odec.close()
 
 
+@pytest.mark.parametrize("env", [
+    {"SKD_R_QKV": "1", "SKD_R_FFN1": "2", "SKD_R_HEAD": "3", "SKD_R_OUT": "1", "SKD_R_FFN2": "2"},
+    {"SKD_U_QKV": "2", "SKD_U_FFN1": "4", "SKD_U_HEAD": "2", "SKD_U_OUT": "2", "SKD_U_FFN2": "4"},
+    {"SKD_W_QKV": "4", "SKD_W_FFN1": "4", "SKD_W_HEAD": "4", "SKD_W_OUT": "4", "SKD_W_FFN2": "4"},
+    {"SKD_S_OUT": "1", "SKD_S_FFN2": "8", "SKD_R_OUT": "4", "SKD_R_FFN2": "4"},
+    {"SKD_ATTN_SPLITS": "1"}, {"SKD_ATTN_SPLITS": "4"}, {"SKD_PREFILL_BATCHED": "0", "SKD_ATTN_SPLITS": "8"},
+])
+def test_launch_shape_overrides(env):
+    # every launch shape the planner can choose (tile rows per workgroup, k-steps per buffer, waves, split-K,
+    # attention splits) computes the same function: forced through the environment overrides on one workload
+    import os
+    shape = MID
+    w = bf16_weights(shape, 51)
+    B, P, N = 20, 37, 70
+    pr = S.make_prompts(B, P, shape.V, 52)
+    mask = S.make_ragged_mask(B, P, 5, P, seed=53)
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update(env)
+    try:
+        compare(shape, w, pr, P, N, 1, 3, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
 def test_vocabulary_above_sampler_limit():
     # the sampling head keeps a row of probabilities in registers: vocabularies above 65536 are refused with
     # SKD_ERR_SHAPE, while the LM head and greedy argmax have no such limit
