@@ -226,6 +226,20 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    # context for the roofline fractions: what a plain library copy reaches on this machine (bytes read + written)
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dst.copy_(src)
+    e0.record()
+    for _ in range(4):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 4 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
+
     shape, B, P, T, n_min, n_max, ragged, *rest = WORKLOADS[args.workload]
     wl = rest[0] if rest else 0
     steps = args.steps if args.steps > 0 else T
@@ -251,7 +265,7 @@ def main():
         "config": {"workload": args.workload, "batch": B, "prompt": P, "decode_steps": T,
                    "schedule": f"linear {n_max}->{n_min} of {shape.L} layers" + (f", {wl} warm-up" if wl else ""),
                    "sum_n": int(sum(skip["layers"]))},
-        "hbm_gbs": gbs, "hbm_frac_of_8TBs": gbs / HBM_PEAK_GBS,
+        "hbm_gbs": gbs, "hbm_frac_of_8TBs": gbs / HBM_PEAK_GBS, "device_copy_read_plus_write_gbs": copy_gbs,
         "algorithmic_gb_per_step": skip["bytes"] / steps / 1e9,
         "prefill_s": skip["prefill_s"],
         "kv_pages_reserved_vs_dense": list(skip["kv_pages"]),
