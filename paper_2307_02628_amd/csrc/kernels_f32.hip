@@ -137,37 +137,42 @@ __global__ void k_f32_argmax(const float *logits, int32_t *tokens, int V) {
 
 // ------------------------------------------------------------------ sampling head (both paths; fp32 logits)
 // Temperature + nucleus (top-p) sampling, one 1024-thread workgroup per row.
-// Thread t keeps tokens [t*C, (t+1)*C) in registers, C = ceil(V / 1024) <= 64.
+// Wave w keeps the contiguous index range [w*R*64, (w+1)*R*64) in registers, R = ceil(V / 1024) <= 64 rows of 64
+// tokens, lane l holding token w*R*64 + 64 i + l of row i (coalesced 256-byte loads).
 //   p_i = exp((z_i - max z) / T);  nucleus = {p_i >= tau}, tau = the largest value whose upper set has mass
 //   >= top_p * sum p  (found bit by bit on the float bit pattern, 31 block sums; tokens tied with tau are in);
 //   token = first index of the nucleus whose running mass (ascending index) exceeds u * mass(nucleus).
 // Every sum is taken in a fixed order, so a given (logits, u) always yields the same token.
 constexpr int SAMPLE_C = 64;
 
+// RC: rows compiled in (>= R); 52 rows cover vocabularies up to 53248 without register spills
+template <int RC>
 __global__ __launch_bounds__(1024) void k_sample_top_p(const float *logits, int V, float inv_temp, float top_p,
                                                        const float *u, int32_t *tokens) {
-  __shared__ float sh[16];
-  __shared__ int first_hit, last_in;
+  __shared__ float sh[16], wmass[16];
+  __shared__ float rows[RC * 64];  // the rows of the one wave that walks its range
+  __shared__ int last_in, hit_tok;
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int C = (V + 1023) / 1024, base = tid * C;
+  const int R = (V + 1023) / 1024, base = wave * R * 64 + lane;
   const float *z = logits + (long)b * V;
-  float p[SAMPLE_C];
+  float p[RC];
   float mx = -3.0e38f;
 #pragma unroll
-  for (int j = 0; j < SAMPLE_C; ++j) {
-    p[j] = (j < C && base + j < V) ? z[base + j] * inv_temp : -3.0e38f;
-    mx = fmaxf(mx, p[j]);
+  for (int i = 0; i < RC; ++i) {
+    p[i] = (i < R && base + 64 * i < V) ? z[base + 64 * i] * inv_temp : -3.0e38f;  // sentinel: no such token
+    mx = fmaxf(mx, p[i]);
   }
   mx = wave_max(mx);
   if (lane == 0) sh[wave] = mx;
+  if (tid == 0) { last_in = -1; hit_tok = -1; }
   __syncthreads();
   mx = sh[0];
   for (int w = 1; w < 16; ++w) mx = fmaxf(mx, sh[w]);
   float loc = 0;
 #pragma unroll
-  for (int j = 0; j < SAMPLE_C; ++j) {
-    p[j] = (j < C && base + j < V) ? expf(p[j] - mx) : 0.f;
-    loc += p[j];
+  for (int i = 0; i < RC; ++i) {
+    p[i] = p[i] > -1.0e38f ? expf(p[i] - mx) : 0.f;
+    loc += p[i];
   }
   const float target = top_p * block_sum(loc, sh);
   unsigned T = 0;
@@ -175,51 +180,72 @@ __global__ __launch_bounds__(1024) void k_sample_top_p(const float *logits, int 
     const unsigned cand = T | (1u << bit);
     float m = 0;
 #pragma unroll
-    for (int j = 0; j < SAMPLE_C; ++j) m += (__float_as_uint(p[j]) >= cand) ? p[j] : 0.f;
+    for (int i = 0; i < RC; ++i) m += (__float_as_uint(p[i]) >= cand) ? p[i] : 0.f;  // absent tokens hold zeros
     if (block_sum(m, sh) >= target) T = cand;  // uniform decision: every thread sees the same sum
   }
+  // nucleus: zero everything else; mass per wave (each wave owns a contiguous index range)
   loc = 0;
+  int last = -1;
 #pragma unroll
-  for (int j = 0; j < SAMPLE_C; ++j) {
-    if (__float_as_uint(p[j]) < T || !(j < C && base + j < V)) p[j] = 0.f;  // outside the nucleus
-    loc += p[j];
+  for (int i = 0; i < RC; ++i) {
+    if (__float_as_uint(p[i]) < T) p[i] = 0.f;
+    loc += p[i];
+    if (p[i] > 0.f) last = base + 64 * i;
   }
-  // exclusive prefix of the per-thread masses in index order
-  float inc = loc;
-  for (int off = 1; off < 64; off <<= 1) {
-    const float t = __shfl_up(inc, off);
-    if (lane >= off) inc += t;
-  }
-  __syncthreads();
-  if (lane == 63) sh[wave] = inc;
-  if (tid == 0) { first_hit = 0x7fffffff; last_in = -1; }
-  __syncthreads();
-  float excl = inc - loc, mass = 0;
-  for (int w = 0; w < 16; ++w) {
-    if (w < wave) excl += sh[w];
-    mass += sh[w];
-  }
-  const float goal = u[b] * mass;
-  float run = excl;
-  int hit = 0x7fffffff, last = -1;
-#pragma unroll
-  for (int j = 0; j < SAMPLE_C; ++j) {
-    if (p[j] > 0.f) {
-      if (hit == 0x7fffffff && run + p[j] > goal) hit = base + j;
-      run += p[j];
-      last = base + j;
-    }
-  }
-  if (hit != 0x7fffffff) atomicMin(&first_hit, hit);
+  loc = wave_sum(loc);
+  __syncthreads();  // sh is free again
+  if (lane == 0) wmass[wave] = loc;
   if (last >= 0) atomicMax(&last_in, last);
   __syncthreads();
-  if (tid == 0) tokens[b] = first_hit != 0x7fffffff ? first_hit : last_in;  // rounding at the very end: last member
+  float mass = 0, before = 0;
+  for (int w = 0; w < 16; ++w) {
+    if (w < wave) before += wmass[w];
+    mass += wmass[w];
+  }
+  const float goal = u[b] * mass;
+  // the wave whose range contains the crossing walks its rows in index order
+  const bool mine = before <= goal && before + wmass[wave] > goal;  // at most one wave: the prefix sums are monotone
+  if (mine) {
+#pragma unroll
+    for (int i = 0; i < RC; ++i) rows[i * 64 + lane] = p[i];  // own lane's column: no barrier needed
+    float run = before;
+    int tok = -1;
+    for (int i = 0; i < R && tok < 0; ++i) {
+      {
+        const float pi = rows[i * 64 + lane];
+        float inc = pi;  // inclusive prefix over the lanes of this row
+        for (int off = 1; off < 64; off <<= 1) {
+          const float t = __shfl_up(inc, off);
+          if (lane >= off) inc += t;
+        }
+        const float row = __shfl(inc, 63);
+        if (run + row > goal) {
+          const unsigned long long over = __ballot(pi > 0.f && run + inc > goal);
+          if (over) tok = wave * R * 64 + 64 * i + (int)__builtin_ctzll(over);
+        }
+        run += row;
+      }
+    }
+    if (tok < 0) {  // rounding between the two summation orders: the last member of this wave's range
+      int wl = last;
+      for (int o = 32; o > 0; o >>= 1) wl = max(wl, __shfl_xor(wl, o));
+      tok = wl;
+    }
+    if (lane == 0) hit_tok = tok;
+  }
+  __syncthreads();
+  if (tid == 0) tokens[b] = hit_tok >= 0 ? hit_tok : last_in;  // rounding at the very end: last member
 }
 
 int sample_top_p(hipStream_t s, const float *logits, int B, int V, float temperature, float top_p, const float *u,
                  int32_t *tokens) {
   if (V > 1024 * SAMPLE_C) return -1;
-  hipLaunchKernelGGL(k_sample_top_p, dim3(B), dim3(1024), 0, s, logits, V, 1.0f / temperature, top_p, u, tokens);
+  const int R = (V + 1023) / 1024;
+  const float it = 1.0f / temperature;
+  if (R <= 16) hipLaunchKernelGGL(k_sample_top_p<16>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  else if (R <= 32) hipLaunchKernelGGL(k_sample_top_p<32>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  else if (R <= 52) hipLaunchKernelGGL(k_sample_top_p<52>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  else hipLaunchKernelGGL(k_sample_top_p<SAMPLE_C>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
   return 0;
 }
 
