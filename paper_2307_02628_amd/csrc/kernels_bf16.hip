@@ -359,16 +359,20 @@ static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid
 }
 template <int MB, int R, int U>
 static void launch_gemm_w(hipStream_t s, const GemmArgs &a, int epi, int waves, dim3 grid) {
-  if (waves >= 8) launch_gemm_epi<MB, R, U, 8>(s, a, epi, grid);
-  else launch_gemm_epi<MB, R, U, 4>(s, a, epi, grid);
+  // 8 batch tiles need 4-wave workgroups: with 8 waves (2 per SIMD, 256 registers each) the accumulators spill
+  if constexpr (MB < 8) {
+    if (waves >= 8) { launch_gemm_epi<MB, R, U, 8>(s, a, epi, grid); return; }
+  }
+  launch_gemm_epi<MB, R, U, 4>(s, a, epi, grid);
 }
 template <int MB, int R>
 static void launch_gemm_u(hipStream_t s, const GemmArgs &a, int epi, int U, int waves, dim3 grid) {
-  // register budget: R * MB accumulators plus two buffers of U * (R + MB) fragments, 4 VGPRs each
-  if constexpr (R * MB + 2 * 4 * (R + MB) <= 56) {
+  // register budget: R * MB accumulators plus two buffers of U * (R + MB) fragments, 4 VGPRs each (beyond 44
+  // units the 8-wave instantiations spill)
+  if constexpr (R * MB + 2 * 4 * (R + MB) <= 44) {
     if (U >= 4) { launch_gemm_w<MB, R, 4>(s, a, epi, waves, grid); return; }
   }
-  if constexpr (R * MB + 2 * 2 * (R + MB) <= 56) {
+  if constexpr (R * MB + 2 * 2 * (R + MB) <= 44) {
     if (U >= 2) { launch_gemm_w<MB, R, 2>(s, a, epi, waves, grid); return; }
   }
   launch_gemm_w<MB, R, 1>(s, a, epi, waves, grid);
