@@ -94,11 +94,16 @@ __device__ inline EpiPre epi_prefetch(const GemmArgs &a, int row, int n0) {
     if (n0 + 3 < a.N) p.bias = *(const floatx4 *)&a.bias[n0];  // N is a multiple of 4 for these
   }
   if constexpr (EPI == EPI_QKV_ROWS) {
-    const int b = row / a.P_pad, pos = row - b * a.P_pad;
-    if (n0 >= a.d && n0 < a.N && row < a.rows && b < a.B && pos < a.P) {
-      const int slot = pos - a.start[b];  // keys are stored by real position; padding columns store nothing
-      p.page = slot >= 0 ? a.bt_layer[(long)b * a.kv.max_pages + slot / a.kv.page_tokens] : -1;
-      p.slot = slot;
+    p.page = -1;
+    if (n0 >= a.d && n0 < a.N && row < a.rows) {
+      const int b = a.rm.seq[row];
+      if (b >= 0) {
+        const int slot = row - a.rm.first_row[b];  // = real position: keys are stored by real position
+        if (slot < a.rm.P - a.rm.start[b]) {       // else padding of the sequence's last 16-row tile
+          p.page = a.bt_layer[(long)b * a.kv.max_pages + slot / a.kv.page_tokens];
+          p.slot = slot;
+        }
+      }
     }
   }
   if constexpr (EPI == EPI_RESID) {
@@ -152,8 +157,6 @@ constexpr int gemm_stage_rows(int waves, int R, int MB) {
 template <>
 __device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, int n0, floatx4 v, const EpiPre &pre) {
   if (n0 >= a.N || row >= a.rows) return;
-  const int b = row / a.P_pad, pos = row - b * a.P_pad;
-  if (b >= a.B || pos >= a.P) return;  // padding rows (of the 16-position tiles, of the last 128-row chunk)
   v += pre.bias;
   const int which = n0 / a.d, within = n0 - which * a.d;
   const uint2 pk = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
@@ -161,7 +164,7 @@ __device__ inline void gemm_epilogue<EPI_QKV_ROWS>(const GemmArgs &a, int row, i
     *(uint2 *)&a.q_out[d_act_index(row, within, a.d)] = pk;
     return;
   }
-  if (pre.page < 0) return;  // padding column
+  if (pre.page < 0) return;  // padding row
   const int h = within / a.kv.dh, e = within - h * a.kv.dh;
   bf16_t *pg = a.kv_pool + (long)pre.page * a.kv.page_elems;
   const int tt = pre.slot % a.kv.page_tokens;
@@ -827,24 +830,26 @@ void bf16_attention(hipStream_t s, const AttnArgs &a) {
 // ------------------------------------------------------------------ causal attention over a whole prompt
 // Same block arithmetic as k_attention, but the 16 MFMA columns now carry 16
 // different queries (consecutive positions of one sequence) instead of one
-// replicated query.  A workgroup takes 64 consecutive positions of one (row b,
-// head h): each of its 4 waves owns one 16-position tile and walks all key
-// blocks of that tile itself (no merge; softmax state per column), and since
+// replicated query.  A workgroup takes 64 consecutive rows of the prompt pass
+// for one head: each of its 4 waves owns one 16-position tile (of one sequence)
+// and walks all key blocks of that tile itself (no merge; softmax state per column), and since
 // the four waves read almost the same keys at almost the same time, most of
-// their K/V loads are served by the CU's L1.  Keys: start[b] .. own position.
+// their K/V loads are served by the CU's L1.  Keys: real positions 0 .. own.
 template <int DH>
 __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   constexpr int QC = DH / 32, VM = DH / 16;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4, col = lane & 15;
-  const int H = a.kv.H, b = blockIdx.x / H, h = blockIdx.x % H, d = H * DH;
-  const int p0 = (blockIdx.y * 4 + wave) * 16;    // first position of this wave's tile
-  if (p0 >= a.P_pad) return;                      // (no barriers below)
-  const long row0 = (long)b * a.P_pad + p0;       // multiple of 16
-  const int j0 = a.start[b];
-  const int my_pos = p0 + col;                    // this column's query position
-  const int last = min(p0 + 15, a.P - 1);         // last real position of the tile
-  const int my_len = my_pos - j0 + 1;             // keys of this query: slots 0 .. my_len-1 (stored by real position)
-  const int blk_lo = 0, blk_hi = last >= j0 ? ((last - j0) >> 5) + 1 : 0;
+  const int H = a.kv.H, h = blockIdx.x, d = H * DH;
+  const long row0 = ((long)blockIdx.y * 4 + wave) * 16;  // first row of this wave's tile
+  if (row0 >= a.rows) return;                            // (no barriers below)
+  const int b = a.rm.seq[row0];
+  if (b < 0) return;                                     // rows past the last sequence
+  const int p0 = (int)(row0 - a.rm.first_row[b]);        // real position of the tile's first query
+  const int len = a.rm.P - a.rm.start[b];                // real positions of this sequence
+  const int my_pos = p0 + col;                           // this column's query position
+  const int last = min(p0 + 15, len - 1);                // last real position of the tile
+  const int my_len = my_pos + 1;                         // keys of this query: real positions 0 .. my_pos
+  const int blk_lo = 0, blk_hi = (last >> 5) + 1;
   const int bpp = a.kv.page_tokens >> 5;
   const int32_t *bt_row = a.bt_layer + (long)b * a.kv.max_pages;
   const float scale = 1.0f / sqrtf((float)DH);
@@ -924,22 +929,23 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
 }
 
 void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a) {
-  const dim3 grid(a.B * a.kv.H, (a.P_pad + 63) / 64);
+  const dim3 grid(a.kv.H, (a.rows + 63) / 64);
   if (a.kv.dh == 64) hipLaunchKernelGGL(k_attention_rows<64>, grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL(k_attention_rows<128>, grid, dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------ row kernels of the batched prompt
-__global__ __launch_bounds__(1024) void k_embed_ln_rows(const int32_t *tokens, const int32_t *start, const bf16_t *tok_emb,
+__global__ __launch_bounds__(1024) void k_embed_ln_rows(const int32_t *tokens, RowMap rm, const bf16_t *tok_emb,
                                                         const bf16_t *pos_emb, const float *g, const float *bt, float *x,
-                                                        bf16_t *a_out, int B, int P, int P_pad, int d, int V) {
+                                                        bf16_t *a_out, int B, int d, int V) {
   __shared__ float sh[16];
-  const int row = blockIdx.x, b = row / P_pad, col = row - b * P_pad, d4 = d >> 2;
-  if (col >= P) return;  // tile padding: rows stay zero
-  int tok = tokens[(long)col * B + b];
+  const int row = blockIdx.x, d4 = d >> 2;
+  const int b = rm.seq[row];
+  if (b < 0) return;  // rows past the last sequence stay zero
+  const int pos = row - rm.first_row[b];  // real position = position id
+  if (pos >= rm.P - rm.start[b]) return;  // padding of the sequence's last 16-row tile: stays zero
+  int tok = tokens[(long)(rm.start[b] + pos) * B + b];
   tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-  int pos = col - start[b];
-  if (pos < 0) pos = 0;
   const uint2 *te = (const uint2 *)(tok_emb + (long)tok * d), *pe = (const uint2 *)(pos_emb + (long)pos * d);
   floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
 #pragma unroll
@@ -1013,16 +1019,16 @@ __global__ __launch_bounds__(1024) void k_ln_rows16(const float *x, const float 
     }
 }
 
-__global__ void k_gather_rows(const float *x_rows, float *x_out, int P_pad, int pos, int d) {
-  const long src = ((long)blockIdx.x * P_pad + pos) * d;
+__global__ void k_gather_rows(const float *x_rows, float *x_out, RowMap rm, int d) {
+  const int b = blockIdx.x;
+  const long src = ((long)rm.first_row[b] + (rm.P - rm.start[b]) - 1) * d;  // the sequence's last prompt position
   for (int k = threadIdx.x; k < d; k += blockDim.x) x_out[(long)blockIdx.x * d + k] = x_rows[src + k];
 }
 
-void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, const int32_t *start, const bf16_t *tok_emb,
-                        const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int P,
-                        int P_pad, int d, int V) {
-  hipLaunchKernelGGL(k_embed_ln_rows, dim3(B * P_pad), dim3(1024), 0, s, tokens, start, tok_emb, pos_emb, g, b, x, a_out,
-                     B, P, P_pad, d, V);
+void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, RowMap rm, int rows, const bf16_t *tok_emb,
+                        const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
+                        int V) {
+  hipLaunchKernelGGL(k_embed_ln_rows, dim3(rows), dim3(1024), 0, s, tokens, rm, tok_emb, pos_emb, g, b, x, a_out, B, d, V);
 }
 void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b, bf16_t *a_out, int rows, int d) {
   if (rows % 16 == 0 && d % 256 == 0 && d <= 256 * LNW_NC) {
@@ -1031,8 +1037,8 @@ void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b,
   }
   hipLaunchKernelGGL(k_ln_rows, dim3(rows), dim3(1024), 0, s, x, g, b, a_out, d);
 }
-void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, int B, int P_pad, int pos, int d) {
-  hipLaunchKernelGGL(k_gather_rows, dim3(B), dim3(256), 0, s, x_rows, x_out, P_pad, pos, d);
+void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, RowMap rm, int B, int d) {
+  hipLaunchKernelGGL(k_gather_rows, dim3(B), dim3(256), 0, s, x_rows, x_out, rm, d);
 }
 
 // ------------------------------------------------------------------ argmax over workgroup partials

@@ -91,6 +91,7 @@ struct skd_state {
   // batched prompt workspace (allocated by the first batched skd_prefill)
   float *pf_x = nullptr;
   bf16_t *pf_a = nullptr, *pf_q = nullptr, *pf_o = nullptr, *pf_u = nullptr;
+  int32_t *pf_seq = nullptr, *pf_first = nullptr;  // row map of the prompt pass (sequence of each row, first row of each sequence)
   int prefill_mode = 1;            // 1 = whole prompt per layer (bf16 path), 0 = column by column
   // sequencing
   bool prefilled = false, have_hidden = false, have_argmax = false;
@@ -575,28 +576,44 @@ static int upload_start(skd_state *st, const std::vector<int32_t> &start) {
 }
 
 // Whole prompt at once, layer by layer (Section 2.3: the prompt needs no generation, so it can be batched over
-// positions): activation rows are (sequence, position) pairs, the projections run on 128-row chunks, attention is
-// causal over the pages the QKV projection has just filled.
+// positions): activation rows are the real (sequence, position) pairs (left padding gets no rows), the projections
+// run on 256 x 256 tiles, attention is causal over the pages the QKV projection has just filled.
 static int prefill_batched(skd_state *st, const int32_t *cols) {
   const skd_config &c = st->cfg;
   const int B = c.batch, P = c.prompt_size, d = c.d_model, f = c.ffn, L = c.L;
   const int P_pad = (P + 15) / 16 * 16;
-  const long rows = (long)B * P_pad, rows_pad = (rows + 255) / 256 * 256;
+  const long cap = ((long)B * P_pad + 255) / 256 * 256;  // workspace rows: every position of every sequence
   hipStream_t s = st->stream;
   if (!st->pf_x) {
-    SKDCHECK(dev_alloc(st, &st->pf_x, (size_t)rows_pad * d));
-    SKDCHECK(dev_alloc(st, &st->pf_a, (size_t)rows_pad * d));
-    SKDCHECK(dev_alloc(st, &st->pf_q, (size_t)rows_pad * d));
-    SKDCHECK(dev_alloc(st, &st->pf_o, (size_t)rows_pad * d));
-    SKDCHECK(dev_alloc(st, &st->pf_u, (size_t)rows_pad * f));
+    SKDCHECK(dev_alloc(st, &st->pf_x, (size_t)cap * d));
+    SKDCHECK(dev_alloc(st, &st->pf_a, (size_t)cap * d));
+    SKDCHECK(dev_alloc(st, &st->pf_q, (size_t)cap * d));
+    SKDCHECK(dev_alloc(st, &st->pf_o, (size_t)cap * d));
+    SKDCHECK(dev_alloc(st, &st->pf_u, (size_t)cap * f));
+    SKDCHECK(dev_alloc(st, &st->pf_seq, (size_t)cap));
+    SKDCHECK(dev_alloc(st, &st->pf_first, (size_t)B));
   }
+  // only real tokens get rows: sequence b owns its P - start[b] positions, padded to whole 16-row tiles
+  std::vector<int32_t> first(B), seq((size_t)cap, -1);
+  long rows = 0;
+  for (int b = 0; b < B; ++b) {
+    const int len = P - st->start_host[b], lp = (len + 15) / 16 * 16;
+    first[b] = (int32_t)rows;
+    std::fill(seq.begin() + rows, seq.begin() + rows + lp, b);
+    rows += lp;
+  }
+  const long rows_pad = (rows + 255) / 256 * 256;
+  HIPCHECK(hipMemcpyAsync(st->pf_seq, seq.data(), (size_t)rows_pad * sizeof(int32_t), hipMemcpyHostToDevice, s));
+  HIPCHECK(hipMemcpyAsync(st->pf_first, first.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s));
+  HIPCHECK(hipStreamSynchronize(s));  // the host vectors go out of scope
+  RowMap rm{st->pf_seq, st->pf_first, st->start_dev, P};
   // padding rows are read by the projections: keep them finite
   HIPCHECK(hipMemsetAsync(st->pf_x, 0, (size_t)rows_pad * d * sizeof(float), s));
   HIPCHECK(hipMemsetAsync(st->pf_a, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
   HIPCHECK(hipMemsetAsync(st->pf_q, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
   HIPCHECK(hipMemsetAsync(st->pf_o, 0, (size_t)rows_pad * d * sizeof(bf16_t), s));
-  bf16_embed_ln_rows(s, cols, st->start_dev, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, st->lw[0].ln1_g,
-                     st->lw[0].ln1_b, st->pf_x, st->pf_a, B, P, P_pad, d, c.vocab);
+  bf16_embed_ln_rows(s, cols, rm, (int)rows, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, st->lw[0].ln1_g,
+                     st->lw[0].ln1_b, st->pf_x, st->pf_a, B, d, c.vocab);
   // 256 x 256 tiles where the shape allows, else 128-row chunks through the skinny kernel
   static const int use_tiles = env_int("SKD_PREFILL_TILES", 1);
   auto proj = [&](const GemmArgs &g, int epi) {
@@ -606,13 +623,13 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
   for (int l = 0; l < L; ++l) {
     const LayerW &w = st->lw[l];
     GemmArgs ga{};
-    ga.B = B; ga.B_pad = 128; ga.rows = (int)rows_pad; ga.P_pad = P_pad; ga.P = P; ga.kv = st->geom; ga.d = d; ga.split = 1;
+    ga.B = B; ga.B_pad = 128; ga.rows = (int)rows_pad; ga.rm = rm; ga.kv = st->geom; ga.d = d; ga.split = 1;
     ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = st->pf_a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d;
-    ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l); ga.start = st->start_dev;
+    ga.q_out = st->pf_q; ga.kv_pool = (bf16_t *)st->pool; ga.bt_layer = bt_layer(st, l);
     if (proj(ga, EPI_QKV_ROWS) < 0) return SKD_ERR_SHAPE;
     AttnRowsArgs aa{};
-    aa.q = st->pf_q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev;
-    aa.B = B; aa.P_pad = P_pad; aa.P = P; aa.kv = st->geom; aa.o = st->pf_o;
+    aa.q = st->pf_q; aa.pool = (const bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.rm = rm;
+    aa.rows = (int)rows; aa.kv = st->geom; aa.o = st->pf_o;
     bf16_attention_rows(s, aa);
     ga.W = (const bf16_t *)w.wo; ga.G = st->p_out.R; ga.A = st->pf_o; ga.bias = w.bo; ga.N = d; ga.K = d; ga.x = st->pf_x;
     if (proj(ga, EPI_RESID) < 0) return SKD_ERR_SHAPE;
@@ -625,7 +642,7 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
     st->kv_len[l] = P;
   }
   // hidden state of the last prompt column, and its final LayerNorm, where the heads expect them
-  bf16_gather_rows(s, st->pf_x, st->x, B, P_pad, P - 1, d);
+  bf16_gather_rows(s, st->pf_x, st->x, rm, B, d);
   bf16_ln_rows(s, st->x, st->lnf_g, st->lnf_b, (bf16_t *)st->a, B, d);
   HIPCHECK(hipGetLastError());
   st->have_hidden = true;

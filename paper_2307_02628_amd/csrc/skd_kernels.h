@@ -49,6 +49,15 @@ int sample_top_p(hipStream_t s, const float *logits, int B, int V, float tempera
 // bytes): one tile is still one 1 KiB B-operand load (lane l reads 16-byte
 // slot (l % 16) * 4 + l / 16), while a producer that owns a row stores 64-byte
 // runs instead of scattered 8- or 16-byte pieces.
+// Rows of the batched prompt pass.  Only real tokens get rows: sequence b owns P - start[b] rows (its real
+// positions, in order), padded to a multiple of 16, starting at first_row[b].
+struct RowMap {
+  const int32_t *seq;        // [rows] sequence of each row (rows past the last sequence: -1)
+  const int32_t *first_row;  // [B] multiple of 16
+  const int32_t *start;      // [B] first real column of each sequence
+  int P;                     // prompt columns
+};
+
 enum GemmEpilogue {
   EPI_PARTIAL = 0,  // fp32 partial sums [split][B_pad][N], no bias
   EPI_QKV = 1,      // + bias; q -> row-major bf16, k/v -> row-major staging rows (filed into the page by bf16_attention)
@@ -65,10 +74,10 @@ struct GemmArgs {
   const float *bias;   // [N] or null
   int N, K, B, B_pad;
   int split;           // workgroups along K (grid.y)
-  // batched prompt processing: activation rows are (sequence b, position pos) pairs, row = b * P_pad + pos,
-  // handled in chunks of B_pad rows along grid.z.  rows = 0: one chunk whose rows are the batch (decode).
-  int rows;            // B * P_pad
-  int P_pad, P;        // positions per sequence (padded to 16) and real prompt length
+  // batched prompt processing: activation rows are the real (sequence, position) pairs of `rm`, handled in
+  // 256 x 256 tiles or in chunks of B_pad rows along grid.z.  rows = 0: one chunk whose rows are the batch (decode).
+  int rows;            // rows of the prompt pass, padded to 256
+  RowMap rm;           // EPI_QKV_ROWS
   float *x;            // EPI_RESID: [rows][N] fp32
   // outputs (by epilogue)
   float *partial;      // EPI_PARTIAL
@@ -76,7 +85,6 @@ struct GemmArgs {
   bf16_t *kv_new;      // EPI_QKV: [B][k | v][d] row-major
   bf16_t *kv_pool;     // EPI_QKV_ROWS
   const int32_t *bt_layer;  // EPI_QKV_ROWS: [B][max_pages]
-  const int32_t *start;     // EPI_QKV_ROWS: [B] first real column of each row (keys are stored by real position)
   int d;               // EPI_QKV, EPI_QKV_ROWS: d_model (N = 3d)
   KvGeom kv;           // EPI_QKV_ROWS
   bf16_t *act_out;     // EPI_RELU
@@ -120,19 +128,19 @@ struct AttnRowsArgs {
   const bf16_t *q;          // activation tiles [rows][d]
   const bf16_t *pool;
   const int32_t *bt_layer;  // [B][max_pages]
-  const int32_t *start;     // [B]
-  int B, P_pad, P;
+  RowMap rm;
+  int rows;                 // multiple of 16
   KvGeom kv;
   bf16_t *o;                // activation tiles [rows][d]
 };
 void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a);
-// Batched prompt row kernels: rows = B * P_pad, tokens laid out [P][B].
-void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, const int32_t *start, const bf16_t *tok_emb,
-                        const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int P,
-                        int P_pad, int d, int V);
+// Batched prompt row kernels; tokens laid out [P][B].
+void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, RowMap rm, int rows, const bf16_t *tok_emb,
+                        const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
+                        int V);
 void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b, bf16_t *a_out, int rows, int d);
-// x_out[b][:] = x_rows[b * P_pad + pos][:]
-void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, int B, int P_pad, int pos, int d);
+// x_out[b][:] = row of sequence b's last prompt position
+void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, RowMap rm, int B, int d);
 void bf16_argmax_final(hipStream_t s, const float *pmax, const int32_t *pidx, int groups, int B_pad, int32_t *tokens,
                        int B);
 
