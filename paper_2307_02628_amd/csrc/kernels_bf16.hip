@@ -35,9 +35,9 @@ __device__ inline float wave_sum_f(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
   return v;
 }
-__device__ inline float block_sum_f(float v, float *sh) {
+// one barrier: `sh` (16 floats) must not have been read since the last barrier of the block
+__device__ inline float block_sum_once(float v, float *sh) {
   v = wave_sum_f(v);
-  __syncthreads();
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
   float r = 0;
@@ -554,7 +554,7 @@ __device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i)
     if ((int)threadIdx.x + 1024 * i < d4) s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
-  const float mean = block_sum_f(s, sh) / d;
+  const float mean = block_sum_once(s, sh) / d;  // sh: 32 floats, one half per reduction, so two barriers in all
   float q = 0;
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i)
@@ -562,7 +562,7 @@ __device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&
       const floatx4 t = v[i] - mean;
       q += (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]);
     }
-  const float rstd = 1.0f / sqrtf(block_sum_f(q, sh) / d + 1e-5f);
+  const float rstd = 1.0f / sqrtf(block_sum_once(q, sh + 16) / d + 1e-5f);
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i) {
     const int c = (int)threadIdx.x + 1024 * i;
@@ -576,7 +576,7 @@ __device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&
 __global__ __launch_bounds__(1024) void k_embed_ln(const int32_t *tokens, const int32_t *start, int t,
                                                    const bf16_t *tok_emb, const bf16_t *pos_emb, const float *g,
                                                    const float *bt, float *x, bf16_t *a_out, int d, int V) {
-  __shared__ float sh[16];
+  __shared__ float sh[32];
   const int b = blockIdx.x, d4 = d >> 2;
   int tok = tokens[b];
   tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
@@ -608,7 +608,7 @@ void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, i
 // x[b][:] += bias + sum_s partial[s][b][:] (fixed order), then LayerNorm
 __global__ __launch_bounds__(1024) void k_reduce_ln(const float *partial, int split, int B_pad, const float *bias,
                                                     float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
-  __shared__ float sh[16];
+  __shared__ float sh[32];
   const int b = blockIdx.x, d4 = d >> 2;
   const floatx4 *p4 = (const floatx4 *)partial;
   floatx4 *x4 = (floatx4 *)x + (long)b * d4;
@@ -938,7 +938,7 @@ void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a) {
 __global__ __launch_bounds__(1024) void k_embed_ln_rows(const int32_t *tokens, RowMap rm, const bf16_t *tok_emb,
                                                         const bf16_t *pos_emb, const float *g, const float *bt, float *x,
                                                         bf16_t *a_out, int B, int d, int V) {
-  __shared__ float sh[16];
+  __shared__ float sh[32];
   const int row = blockIdx.x, d4 = d >> 2;
   const int b = rm.seq[row];
   if (b < 0) return;  // rows past the last sequence stay zero
@@ -964,7 +964,7 @@ __global__ __launch_bounds__(1024) void k_embed_ln_rows(const int32_t *tokens, R
 }
 
 __global__ __launch_bounds__(1024) void k_ln_rows(const float *x, const float *g, const float *bt, bf16_t *a_out, int d) {
-  __shared__ float sh[16];
+  __shared__ float sh[32];
   const int row = blockIdx.x, d4 = d >> 2;
   floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
 #pragma unroll
