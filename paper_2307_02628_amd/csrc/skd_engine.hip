@@ -202,10 +202,17 @@ int plan_waves(int B_pad) { return B_pad >= 128 ? 4 : 8; }
 GemmPlan plan_direct(int N, int B_pad) {  // whole K inside the workgroup
   GemmPlan p;
   p.waves = plan_waves(B_pad);
-  p.R = 1;
-  for (int R = 4; R >= 1; --R)  // the largest R that still gives every CU a workgroup
-    if (bf16_gemm_groups(N, R) >= 256) { p.R = R; break; }
   p.split = 1;
+  p.R = 4;
+  if (bf16_gemm_groups(N, 4) >= 512) return p;  // several rounds of workgroups: take the fewest activation re-reads
+  // one or two rounds: the R that keeps the largest share of the 256 CUs busy over whole rounds; ties go to the
+  // larger R (measured: 768 tiles -> R = 3, 256 workgroups; 384 tiles -> R = 2, 192 workgroups beats 384)
+  double best = -1.0;
+  for (int R = 1; R <= 4; ++R) {
+    const int g = bf16_gemm_groups(N, R);
+    const double e = (double)g / (256.0 * ((g + 255) / 256));
+    if (e >= best) { best = e; p.R = R; }
+  }
   return p;
 }
 GemmPlan plan_split(int N, int K, int B_pad) {  // partial sums, reduced by the LayerNorm kernel
