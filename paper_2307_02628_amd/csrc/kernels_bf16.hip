@@ -215,7 +215,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) w[u][r] = Wl[woff[r] + (long)(j * U + u) * kstride];
+      for (int r = 0; r < R; ++r) w[u][r] = __builtin_nontemporal_load(&Wl[woff[r] + (long)(j * U + u) * kstride]);
 #pragma unroll
       for (int m = 0; m < MB; ++m) x[u][m] = Ab[((long)m * Kf + j * U + u) * 64];
     }
@@ -701,9 +701,9 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
-      for (int c = 0; c < QC; ++c) kf[tl][c] = kp[(tl * QC + c) * 64];
+      for (int c = 0; c < QC; ++c) kf[tl][c] = __builtin_nontemporal_load(&kp[(tl * QC + c) * 64]);
 #pragma unroll
-    for (int m = 0; m < VM; ++m) vf[m] = kp[4 * DH + m * 64];
+    for (int m = 0; m < VM; ++m) vf[m] = __builtin_nontemporal_load(&kp[4 * DH + m * 64]);
 
     floatx4 S[2];
 #pragma unroll
