@@ -129,6 +129,17 @@ def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, war
            "bytes": sum(step_bytes(shape, layers[k], sum_len[k]) for k in range(steps)),
            "kv_pages": dec.kv_pages()}
     if profile:
+        # the same timed region four more times (the line's `value` stays the first, contract-defined one)
+        reps = [ms]
+        for _ in range(4):
+            dec.rewind(P)
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            run(0, steps)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            reps.append(ev0.elapsed_time(ev1))
+        out["repeat_ms"] = reps
         dec.rewind(P)
         dec.profile_enable(True)
         run(0, steps)
@@ -277,6 +288,10 @@ def main():
         res["speedup_vs_full_depth"] = tok_s / ftok
         res["ideal_layer_ratio"] = shape.L * steps / sum(skip["layers"])
         res["ideal_byte_ratio"] = full["bytes"] / skip["bytes"]
+    if "repeat_ms" in skip:
+        r = np.array(skip["repeat_ms"], dtype=np.float64) / steps
+        res["ms_per_step_repeats"] = {"n": int(r.size), "median": float(np.median(r)), "min": float(r.min()),
+                                      "max": float(r.max())}
     if "step_ms" in skip:
         ns = np.array(skip["layers"], dtype=np.float64)
         ms = np.array(skip["step_ms"], dtype=np.float64)

@@ -219,7 +219,9 @@ GemmPlan plan_split(int N, int K, int B_pad) {  // partial sums, reduced by the 
   GemmPlan p;
   p.waves = plan_waves(B_pad);
   const int Kf = K / 32;
-  p.R = 4;
+  // tile rows per workgroup: enough that the activation re-reads (B_pad / (16 R) of the weight bytes) stay at
+  // half the weight stream; more rows than that only force a deeper split, whose partials the reducer pays for
+  p.R = B_pad >= 32 ? 4 : 2;
   while (p.R > 1 && N % (16 * p.R)) --p.R;
   for (;;) {
     int S = 1;
