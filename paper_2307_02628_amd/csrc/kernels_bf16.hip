@@ -833,8 +833,8 @@ void bf16_attention(hipStream_t s, const AttnArgs &a) {
 // replicated query.  A workgroup takes 64 consecutive rows of the prompt pass
 // for one head: each of its 4 waves owns one 16-position tile (of one sequence)
 // and walks all key blocks of that tile itself (no merge; softmax state per column), and since
-// the four waves read almost the same keys at almost the same time, most of
-// their K/V loads are served by the CU's L1.  Keys: real positions 0 .. own.
+// the four waves read almost the same keys at almost the same time, all but
+// the first of those loads are cache hits (L2 at worst).  Keys: real positions 0 .. own.
 template <int DH>
 __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
   constexpr int QC = DH / 32, VM = DH / 16;
