@@ -693,18 +693,18 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
   for (int m = 0; m < VM; ++m) O[m] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m_run = -1.0e30f, l_run = 0.f;  // l_run: this lane group's share of the denominator
 
-  for (int blk = my_lo + wave; blk < my_hi; blk += 4) {
+  auto load_blk = [&](int blk, bf16x8(&kf)[2][QC], bf16x8(&vf)[VM]) {
     const int page = bt_row[blk / bpp];
     const bf16x8 *kp = (const bf16x8 *)(a.pool + (long)page * a.kv.page_elems + (long)h * (a.kv.page_tokens * DH * 2) +
                                         (long)(blk % bpp) * (64 * DH)) + lane;
-    bf16x8 kf[2][QC], vf[VM];
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
       for (int c = 0; c < QC; ++c) kf[tl][c] = __builtin_nontemporal_load(&kp[(tl * QC + c) * 64]);
 #pragma unroll
     for (int m = 0; m < VM; ++m) vf[m] = __builtin_nontemporal_load(&kp[4 * DH + m * 64]);
-
+  };
+  auto use_blk = [&](int blk, bf16x8(&kf)[2][QC], bf16x8(&vf)[VM]) {
     floatx4 S[2];
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl) {
@@ -746,6 +746,31 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
     for (int m = 0; m < VM; ++m) {
       O[m] *= alpha;
       O[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[m], pv, O[m], 0, 0, 0);
+    }
+  };
+  // With 64-wide heads a second block fits in the registers (four waves per SIMD leave 128), so the next block's
+  // loads are in flight while this one is used: rows of a few blocks per wave are otherwise one full memory
+  // latency per block.  128-wide heads would need 64 more registers than four waves per SIMD allow.
+  if constexpr (DH == 64) {
+    bf16x8 kf0[2][QC], vf0[VM], kf1[2][QC], vf1[VM];
+    int blk = my_lo + wave;
+    if (blk < my_hi) {
+      load_blk(blk, kf0, vf0);
+      while (true) {
+        if (blk + 4 < my_hi) load_blk(blk + 4, kf1, vf1);
+        use_blk(blk, kf0, vf0);
+        if (blk + 4 >= my_hi) break;
+        if (blk + 8 < my_hi) load_blk(blk + 8, kf0, vf0);
+        use_blk(blk + 4, kf1, vf1);
+        if (blk + 8 >= my_hi) break;
+        blk += 8;
+      }
+    }
+  } else {
+    for (int blk = my_lo + wave; blk < my_hi; blk += 4) {
+      bf16x8 kf[2][QC], vf[VM];
+      load_blk(blk, kf, vf);
+      use_blk(blk, kf, vf);
     }
   }
   // O[m][i] = sum_key p * v[key][16*m + 4*grp + i]   (same in all 16 columns)
