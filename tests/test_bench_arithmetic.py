@@ -54,3 +54,12 @@ def test_step_bytes_of_the_contract_workloads(name, sum_n, skip_gb, full_gb, lay
     assert abs(skip / T / 1e9 - skip_gb) < 0.01
     assert abs(full / T / 1e9 - full_gb) < 0.01
     assert abs(shape.L * T / sum(n) - layer_ratio) < 5e-4
+
+
+def test_more_than_one_gpu_is_refused():
+    import subprocess
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
