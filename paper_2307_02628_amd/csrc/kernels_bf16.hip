@@ -636,17 +636,19 @@ void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, c
 }
 
 // ------------------------------------------------------------------ decode attention over the paged KV cache
-// One workgroup (4 waves) per (row, head, split).  Wave w takes 32-key blocks
-// first + w, first + w + 4, ...; each block is 2 K tiles (QK^T: 2 * DH/32
-// MFMAs, q replicated over the 16 MFMA columns) and one V block (DH/16 MFMAs).
-// Online softmax per wave in fp32; the four waves (and, with splits > 1, the
-// workgroups of one head) are merged with the usual max / sum rescaling.
+// One workgroup of NW waves (4, 8 or 16) per (row, head, split).  Wave w takes
+// 32-key blocks first + w, first + w + NW, ...; each block is 2 K tiles (QK^T:
+// 2 * DH/32 MFMAs, q replicated over the 16 MFMA columns) and one V block
+// (DH/16 MFMAs).  Online softmax per wave in fp32; the waves (and, with
+// splits > 1, the workgroups of one head) are merged with the usual max / sum
+// rescaling.  Batches with few (row, head) pairs get their 16 waves per CU from
+// wider workgroups rather than from splits, which need a second kernel.
 // Four waves per SIMD are required: with three the kernel is 13 % slower.
-template <int DH>
-__global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64, 16 / NW) void k_attention(AttnArgs a) {
   constexpr int QC = DH / 32, VM = DH / 16;
-  __shared__ float sm_m[4], sm_l[4], sm_dot[4];
-  __shared__ float sm_o[4][DH];
+  __shared__ float sm_m[NW], sm_l[NW], sm_dot[NW];
+  __shared__ float sm_o[NW][DH];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4;
   const int H = a.kv.H, h = blockIdx.x % H, d = H * DH;
   // longest rows are dispatched first, so that the last workgroups to start are the short ones
@@ -757,17 +759,17 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
     if (blk < my_hi) {
       load_blk(blk, kf0, vf0);
       while (true) {
-        if (blk + 4 < my_hi) load_blk(blk + 4, kf1, vf1);
+        if (blk + NW < my_hi) load_blk(blk + NW, kf1, vf1);
         use_blk(blk, kf0, vf0);
-        if (blk + 4 >= my_hi) break;
-        if (blk + 8 < my_hi) load_blk(blk + 8, kf0, vf0);
-        use_blk(blk + 4, kf1, vf1);
-        if (blk + 8 >= my_hi) break;
-        blk += 8;
+        if (blk + NW >= my_hi) break;
+        if (blk + 2 * NW < my_hi) load_blk(blk + 2 * NW, kf0, vf0);
+        use_blk(blk + NW, kf1, vf1);
+        if (blk + 2 * NW >= my_hi) break;
+        blk += 2 * NW;
       }
     }
   } else {
-    for (int blk = my_lo + wave; blk < my_hi; blk += 4) {
+    for (int blk = my_lo + wave; blk < my_hi; blk += NW) {
       bf16x8 kf[2][QC], vf[VM];
       load_blk(blk, kf, vf);
       use_blk(blk, kf, vf);
@@ -791,7 +793,8 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
   __syncthreads();
   if (threadIdx.x < DH) {
     const int e = threadIdx.x;
-    float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+    float M = sm_m[0];
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w]);
     float s_t = 0.f;
     if (with_new) {
       for (int w = 0; w < DH / 64; ++w) s_t += sm_dot[w];
@@ -799,7 +802,7 @@ __global__ __launch_bounds__(256, 4) void k_attention(AttnArgs a) {
       M = fmaxf(M, s_t);
     }
     float num = 0.f, den = 0.f;
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float f = __expf(sm_m[w] - M);
       num += f * sm_o[w][e];
       den += f * sm_l[w];
@@ -843,11 +846,16 @@ __global__ void k_attn_merge(AttnArgs a) {
 
 void bf16_attention(hipStream_t s, const AttnArgs &a) {
   const dim3 grid(a.B * a.kv.H, a.splits);
+  const int nw = a.waves >= 16 ? 16 : a.waves >= 8 ? 8 : 4;
   if (a.kv.dh == 64) {
-    hipLaunchKernelGGL(k_attention<64>, grid, dim3(256), 0, s, a);
+    if (nw == 16) hipLaunchKernelGGL((k_attention<64, 16>), grid, dim3(1024), 0, s, a);
+    else if (nw == 8) hipLaunchKernelGGL((k_attention<64, 8>), grid, dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((k_attention<64, 4>), grid, dim3(256), 0, s, a);
     if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<64>, dim3(a.B * a.kv.H), dim3(64), 0, s, a);
   } else {
-    hipLaunchKernelGGL(k_attention<128>, grid, dim3(256), 0, s, a);
+    if (nw == 16) hipLaunchKernelGGL((k_attention<128, 16>), grid, dim3(1024), 0, s, a);
+    else if (nw == 8) hipLaunchKernelGGL((k_attention<128, 8>), grid, dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((k_attention<128, 4>), grid, dim3(256), 0, s, a);
     if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<128>, dim3(a.B * a.kv.H), dim3(128), 0, s, a);
   }
 }

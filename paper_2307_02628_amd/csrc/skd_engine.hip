@@ -87,7 +87,7 @@ struct skd_state {
   int32_t *pidx = nullptr;
   // plans (bf16)
   GemmPlan p_qkv, p_out, p_ffn1, p_ffn2, p_head;
-  int max_split = 1, attn_splits = 1;
+  int max_split = 1, attn_splits = 1, attn_waves = 4;
   // batched prompt workspace (allocated by the first batched skd_prefill)
   float *pf_x = nullptr;
   bf16_t *pf_a = nullptr, *pf_q = nullptr, *pf_o = nullptr, *pf_u = nullptr;
@@ -391,7 +391,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       if (grc < 0) return SKD_ERR_SHAPE;
       AttnArgs aa{};
       aa.q = q; aa.kv_new = st->kv_new; aa.pool = (bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->ragged ? st->order_dev : nullptr;
-      aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
+      aa.t = t; aa.B = B; aa.splits = st->attn_splits; aa.waves = st->attn_waves; aa.kv = st->geom; aa.o = o; aa.part = st->attn_part;
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
       ga.W = (const bf16_t *)w.wo; ga.G = st->p_out.R; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
@@ -516,9 +516,14 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
     st->prefill_mode = env_int("SKD_PREFILL_BATCHED", 1) != 0 ? 1 : 0;
     st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
     // split the key range of one head over several workgroups only when rows*heads alone cannot fill the chip
-    int splits = 1;
-    while (B * c.n_heads * splits < 512 && splits < 8) splits *= 2;
+    // decode attention wants 16 waves on every CU: few (row, head) pairs get wider workgroups first (merged in
+    // LDS), then splits of the key range (merged by a second kernel)
+    int waves = 4, splits = 1;
+    while (B * c.n_heads * waves < 4096 && waves < 16) waves *= 2;
+    while (B * c.n_heads * waves * splits < 4096 && splits < 8) splits *= 2;
+    ov("SKD_ATTN_WAVES", waves, 4, 16);
     ov("SKD_ATTN_SPLITS", splits, 1, 16);
+    st->attn_waves = waves;
     st->attn_splits = splits;
     bf16_t *t16 = nullptr;
     A(&t16, (size_t)Bp * d); st->a = t16; if (rc == SKD_OK) rc = hipMemsetAsync(st->a, 0, (size_t)Bp * d * 2, st->stream) == hipSuccess ? SKD_OK : SKD_ERR_HIP;
