@@ -374,10 +374,12 @@ def test_kv_page_contents_match_oracle(shape, batched):
     {"SKD_W_QKV": "4", "SKD_W_FFN1": "4", "SKD_W_HEAD": "4", "SKD_W_OUT": "4", "SKD_W_FFN2": "4"},
     {"SKD_S_OUT": "1", "SKD_S_FFN2": "8", "SKD_R_OUT": "4", "SKD_R_FFN2": "4"},
     {"SKD_ATTN_SPLITS": "1"}, {"SKD_ATTN_SPLITS": "4"}, {"SKD_PREFILL_BATCHED": "0", "SKD_ATTN_SPLITS": "8"},
+    {"SKD_ATTN_WAVES": "4", "SKD_ATTN_SPLITS": "2"}, {"SKD_ATTN_WAVES": "8", "SKD_ATTN_SPLITS": "1"},
+    {"SKD_ATTN_WAVES": "16", "SKD_ATTN_SPLITS": "3"},
 ])
 def test_launch_shape_overrides(env):
     # every launch shape the planner can choose (tile rows per workgroup, k-steps per buffer, waves, split-K,
-    # attention splits) computes the same function: forced through the environment overrides on one workload
+    # attention waves and splits) computes the same function: forced through the environment overrides on one workload
     import os
     shape = MID
     w = bf16_weights(shape, 51)
