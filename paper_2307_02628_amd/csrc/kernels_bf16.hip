@@ -540,9 +540,9 @@ int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epi) {
 }
 
 // ------------------------------------------------------------------ row kernels: embedding / split-K reduce, + LayerNorm
-// One 1024-thread workgroup per batch row.  These kernels move < 5 MB and are
+// One workgroup per batch row, one thread per float4 chunk up to 1024 threads.  These kernels move < 5 MB and are
 // pure latency chains, so each thread keeps its share of the row in registers
-// (float4 chunk c = threadIdx.x + 1024 * i, rows up to 16384 wide), issues
+// (float4 chunk c = threadIdx.x + blockDim.x * i, rows up to 16384 wide), issues
 // every global load it will ever need up front, and the row never touches LDS.
 constexpr int LN_NC = 4;
 
@@ -553,25 +553,28 @@ __device__ inline void ln_finish_row(const floatx4 (&v)[LN_NC], const floatx4 (&
   float s = 0;
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i)
-    if ((int)threadIdx.x + 1024 * i < d4) s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    if ((int)(threadIdx.x + blockDim.x * i) < d4) s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
   const float mean = block_sum_once(s, sh) / d;  // sh: 32 floats, one half per reduction, so two barriers in all
   float q = 0;
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i)
-    if ((int)threadIdx.x + 1024 * i < d4) {
+    if ((int)(threadIdx.x + blockDim.x * i) < d4) {
       const floatx4 t = v[i] - mean;
       q += (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]);
     }
   const float rstd = 1.0f / sqrtf(block_sum_once(q, sh + 16) / d + 1e-5f);
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i) {
-    const int c = (int)threadIdx.x + 1024 * i;
+    const int c = (int)(threadIdx.x + blockDim.x * i);
     if (c < d4) {
       const floatx4 y = (v[i] - mean) * rstd * gv[i] + bv[i];
       *(uint2 *)&a_out[d_act_index(b, 4 * c, d)] = make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
     }
   }
 }
+
+// threads of a row workgroup: one per float4 chunk, whole waves, at most 1024 (narrow rows: fewer waves at the barriers)
+static int row_threads(int d) { return d / 4 >= 1024 ? 1024 : (d / 4 + 63) / 64 * 64; }
 
 __global__ __launch_bounds__(1024) void k_embed_ln(const int32_t *tokens, const int32_t *start, int t,
                                                    const bf16_t *tok_emb, const bf16_t *pos_emb, const float *g,
@@ -586,7 +589,7 @@ __global__ __launch_bounds__(1024) void k_embed_ln(const int32_t *tokens, const 
   floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i) {
-    const int c = (int)threadIdx.x + 1024 * i;
+    const int c = (int)(threadIdx.x + blockDim.x * i);
     if (c < d4) {
       const uint2 a = te[c], p = pe[c];
       gv[i] = ((const floatx4 *)g)[c];
@@ -602,7 +605,7 @@ __global__ __launch_bounds__(1024) void k_embed_ln(const int32_t *tokens, const 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
                    const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
                    int V) {
-  hipLaunchKernelGGL(k_embed_ln, dim3(B), dim3(1024), 0, s, tokens, start, t, tok_emb, pos_emb, g, b, x, a_out, d, V);
+  hipLaunchKernelGGL(k_embed_ln, dim3(B), dim3(row_threads(d)), 0, s, tokens, start, t, tok_emb, pos_emb, g, b, x, a_out, d, V);
 }
 
 // x[b][:] += bias + sum_s partial[s][b][:] (fixed order), then LayerNorm
@@ -615,7 +618,7 @@ __global__ __launch_bounds__(1024) void k_reduce_ln(const float *partial, int sp
   floatx4 v[LN_NC], gv[LN_NC], bv[LN_NC];
 #pragma unroll
   for (int i = 0; i < LN_NC; ++i) {
-    const int c = (int)threadIdx.x + 1024 * i;
+    const int c = (int)(threadIdx.x + blockDim.x * i);
     if (c < d4) {
       const floatx4 xv = x4[c], bias4 = ((const floatx4 *)bias)[c];
       gv[i] = ((const floatx4 *)g)[c];
@@ -632,7 +635,7 @@ __global__ __launch_bounds__(1024) void k_reduce_ln(const float *partial, int sp
 
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d) {
-  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(1024), 0, s, partial, split, B_pad, bias, x, g, b, a_out, d);
+  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(row_threads(d)), 0, s, partial, split, B_pad, bias, x, g, b, a_out, d);
 }
 
 // ------------------------------------------------------------------ decode attention over the paged KV cache
