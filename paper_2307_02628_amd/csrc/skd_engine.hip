@@ -203,8 +203,10 @@ GemmPlan plan_direct(int N, int B_pad) {  // whole K inside the workgroup
   GemmPlan p;
   p.waves = plan_waves(B_pad);
   p.split = 1;
-  p.R = 4;
-  if (bf16_gemm_groups(N, 4) >= 512) return p;  // several rounds of workgroups: take the fewest activation re-reads
+  // several rounds of workgroups (the LM head): tile rows that keep the activation re-reads at half the weight
+  // stream; with one batch tile, 2 rows do that and leave twice the workgroups to even out the last round
+  p.R = B_pad >= 32 ? 4 : 2;
+  if (bf16_gemm_groups(N, p.R) >= 512) return p;
   // one or two rounds: the R that keeps the largest share of the 256 CUs busy over whole rounds; ties go to the
   // larger R (measured: 768 tiles -> R = 3, 256 workgroups; 384 tiles -> R = 2, 192 workgroups beats 384)
   double best = -1.0;
