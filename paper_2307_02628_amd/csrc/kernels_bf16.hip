@@ -639,7 +639,7 @@ void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, c
 }
 
 // ------------------------------------------------------------------ decode attention over the paged KV cache
-// One workgroup of NW waves (4, 8 or 16) per (row, head, split).  Wave w takes
+// One workgroup of NW waves (2, 4, 8 or 16) per (row, head, split).  Wave w takes
 // 32-key blocks first + w, first + w + NW, ...; each block is 2 K tiles (QK^T:
 // 2 * DH/32 MFMAs, q replicated over the 16 MFMA columns) and one V block
 // (DH/16 MFMAs).  Online softmax per wave in fp32; the waves (and, with
@@ -648,7 +648,7 @@ void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, c
 // wider workgroups rather than from splits, which need a second kernel.
 // Four waves per SIMD are required: with three the kernel is 13 % slower.
 template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64, 16 / NW) void k_attention(AttnArgs a) {
+__global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 waves per SIMD whatever the workgroup width
   constexpr int QC = DH / 32, VM = DH / 16;
   __shared__ float sm_m[NW], sm_l[NW], sm_dot[NW];
   __shared__ float sm_o[NW][DH];
@@ -849,15 +849,17 @@ __global__ void k_attn_merge(AttnArgs a) {
 
 void bf16_attention(hipStream_t s, const AttnArgs &a) {
   const dim3 grid(a.B * a.kv.H, a.splits);
-  const int nw = a.waves >= 16 ? 16 : a.waves >= 8 ? 8 : 4;
+  const int nw = a.waves >= 16 ? 16 : a.waves >= 8 ? 8 : a.waves >= 4 ? 4 : 2;
   if (a.kv.dh == 64) {
     if (nw == 16) hipLaunchKernelGGL((k_attention<64, 16>), grid, dim3(1024), 0, s, a);
     else if (nw == 8) hipLaunchKernelGGL((k_attention<64, 8>), grid, dim3(512), 0, s, a);
+    else if (nw == 2) hipLaunchKernelGGL((k_attention<64, 2>), grid, dim3(128), 0, s, a);
     else hipLaunchKernelGGL((k_attention<64, 4>), grid, dim3(256), 0, s, a);
     if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<64>, dim3(a.B * a.kv.H), dim3(64), 0, s, a);
   } else {
     if (nw == 16) hipLaunchKernelGGL((k_attention<128, 16>), grid, dim3(1024), 0, s, a);
     else if (nw == 8) hipLaunchKernelGGL((k_attention<128, 8>), grid, dim3(512), 0, s, a);
+    else if (nw == 2) hipLaunchKernelGGL((k_attention<128, 2>), grid, dim3(128), 0, s, a);
     else hipLaunchKernelGGL((k_attention<128, 4>), grid, dim3(256), 0, s, a);
     if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<128>, dim3(a.B * a.kv.H), dim3(128), 0, s, a);
   }

@@ -118,7 +118,7 @@ struct AttnArgs {
   const int32_t *order;     // [B] rows sorted by descending length: workgroup x/H handles row order[x/H] (null = identity)
   int t;                    // position being processed: cached keys start[b] .. t-1, plus t itself from kv_new
   int B, splits;
-  int waves;                // waves per workgroup: 4, 8 or 16
+  int waves;                // waves per workgroup: 2, 4, 8 or 16
   KvGeom kv;
   bf16_t *o;                // activation tiles [B_pad][d]
   float *part;              // splits > 1: [splits][B*H][dh + 2]

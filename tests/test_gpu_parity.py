@@ -375,7 +375,7 @@ def test_kv_page_contents_match_oracle(shape, batched):
     {"SKD_S_OUT": "1", "SKD_S_FFN2": "8", "SKD_R_OUT": "4", "SKD_R_FFN2": "4"},
     {"SKD_ATTN_SPLITS": "1"}, {"SKD_ATTN_SPLITS": "4"}, {"SKD_PREFILL_BATCHED": "0", "SKD_ATTN_SPLITS": "8"},
     {"SKD_ATTN_WAVES": "4", "SKD_ATTN_SPLITS": "2"}, {"SKD_ATTN_WAVES": "8", "SKD_ATTN_SPLITS": "1"},
-    {"SKD_ATTN_WAVES": "16", "SKD_ATTN_SPLITS": "3"},
+    {"SKD_ATTN_WAVES": "16", "SKD_ATTN_SPLITS": "3"}, {"SKD_ATTN_WAVES": "2"},
 ])
 def test_launch_shape_overrides(env):
     # every launch shape the planner can choose (tile rows per workgroup, k-steps per buffer, waves, split-K,
