@@ -415,20 +415,31 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
 // With thousands of activation rows the projections are compute-bound, and the
 // skinny kernel above (every wave fetching its own operands) is limited by
 // L2-to-CU traffic.  Here a workgroup of 8 waves owns a 256 x 256 output tile
-// (16 weight tiles x 16 activation-row tiles); operand fragments of two k-steps
-// (64 KiB) are staged in LDS, double-buffered, and each wave accumulates a
-// 64 x 128 sub-tile (4 x 8 MFMA tiles, 128 accumulator registers), reading 12
-// fragments from LDS per 32 MFMAs.  Tiled operands make every global
-// load, LDS store and LDS read a contiguous 1 KiB per wave.
-constexpr int TILE_KC = 2;   // k-steps per stage
-constexpr int TILE_FR = 32;  // fragments per k-step: 16 weight tiles, then 16 activation-row tiles
+// (16 weight tiles x 16 activation-row tiles).  The operand fragments of one
+// k-step (32 KiB) form a stage; a ring of 4 stages lives in LDS and is filled by
+// LDS-direct global loads (each lane supplies a global address, its 16 bytes
+// land at the wave's LDS base + 16 * lane: fragments arrive ready-made and no
+// register holds data in flight), three stages ahead of the one being
+// multiplied.  Each wave accumulates a 64 x 128 sub-tile (4 x 8 MFMA tiles, 128
+// accumulator registers), reading 12 fragments from LDS per 32 MFMAs.
+constexpr int TILE_NS = 4;   // ring stages
+constexpr int TILE_FR = 32;  // fragments per stage: 16 weight tiles, then 16 activation-row tiles
+
+// wait until at most n of this wave's vector-memory operations are outstanding (they complete in order)
+__device__ inline void wait_vmcnt_le(int n) {
+  switch (n) {  // s_waitcnt immediate: vmcnt in bits 3:0 (and 15:14), no wait on the export and LDS counters
+    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F78); break;  // 8
+  }
+}
 
 template <int EPI>
 __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
-  extern __shared__ bf16x8 tile_lds[];  // [2 stages][TILE_KC][TILE_FR][64 lanes]
+  extern __shared__ bf16x8 tile_lds[];  // [TILE_NS stages][TILE_FR][64 lanes]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wr = wave >> 1, wc = wave & 1;  // sub-tile: weight tiles 4wr .. 4wr+3, activation tiles 8wc .. 8wc+7
-  const int Kf = a.K >> 5, nst = Kf / TILE_KC;
+  const int Kf = a.K >> 5;
 
   // workgroup -> output tile.  Workgroups are dealt to the 8 XCDs round-robin; the ones that share an XCD (and
   // its L2) at any moment should share operands, so each XCD walks its own contiguous range of tiles in blocks
@@ -445,24 +456,24 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     }
   }
 
-  // this wave's share of a stage's global loads: 8 fragments, all weight or all activation tiles of one k-step
-  const int ld_kk = wave >> 2, ld_is_a = (wave >> 1) & 1, ld_t0 = (wave & 1) * 8;
-  const bf16x8 *src[8];
+  // this wave's share of a stage: 4 fragments; waves 0..3 fetch the weight tiles, waves 4..7 the activation tiles
+  const int ld_is_a = wave >> 2, ld_t0 = (wave & 3) * 4;
+  const bf16x8 *src[4];
   long sstride;
   if (!ld_is_a) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 4; ++i) {
       const int T = tn * 16 + ld_t0 + i;
-      src[i] = (const bf16x8 *)a.W + (((long)(T / a.G) * Kf + ld_kk) * a.G + T % a.G) * 64 + lane;
+      src[i] = (const bf16x8 *)a.W + (((long)(T / a.G) * Kf) * a.G + T % a.G) * 64 + lane;
     }
-    sstride = (long)TILE_KC * a.G * 64;
+    sstride = (long)a.G * 64;
   } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i)  // fetched in MFMA lane order, so that LDS holds ready-made fragments
-      src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf + ld_kk) * 64 + act_lane(lane);
-    sstride = (long)TILE_KC * 64;
+    for (int i = 0; i < 4; ++i)  // fetched in MFMA lane order, so that LDS holds ready-made fragments
+      src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf) * 64 + act_lane(lane);
+    sstride = 64;
   }
-  const int dst0 = (ld_kk * TILE_FR + ld_is_a * 16 + ld_t0) * 64 + lane;  // + i * 64, + stage * TILE_KC * TILE_FR * 64
+  const int dfrag = ld_is_a * 16 + ld_t0;
 
   floatx4 acc[4][8];
 #pragma unroll
@@ -470,39 +481,42 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 #pragma unroll
     for (int m = 0; m < 8; ++m) acc[r][m] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 stg[8];
-  auto gload = [&](int st) {
+  auto issue = [&](int st) {  // 4 vector-memory operations per wave and stage
+    bf16x8 *dst = tile_lds + ((st % TILE_NS) * TILE_FR + dfrag) * 64;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) stg[i] = src[i][(long)st * sstride];
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) tile_lds[buf * (TILE_KC * TILE_FR * 64) + dst0 + i * 64] = stg[i];
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + (long)st * sstride),
+                                       (__attribute__((address_space(3))) void *)(dst + i * 64), 16, 0, 0);
   };
   auto compute = [&](int buf) {
+    const bf16x8 *base = tile_lds + buf * (TILE_FR * 64) + lane;
+    bf16x8 wf[4], xf[8];
 #pragma unroll
-    for (int kk = 0; kk < TILE_KC; ++kk) {
-      const bf16x8 *base = tile_lds + (buf * TILE_KC + kk) * (TILE_FR * 64) + lane;
-      bf16x8 wf[4], xf[8];
+    for (int r = 0; r < 4; ++r) wf[r] = base[(wr * 4 + r) * 64];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) wf[r] = base[(wr * 4 + r) * 64];
+    for (int m = 0; m < 8; ++m) xf[m] = base[(16 + wc * 8 + m) * 64];
 #pragma unroll
-      for (int m = 0; m < 8; ++m) xf[m] = base[(16 + wc * 8 + m) * 64];
+    for (int r = 0; r < 4; ++r)
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int m = 0; m < 8; ++m) acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[r], xf[m], acc[r][m], 0, 0, 0);
-    }
+      for (int m = 0; m < 8; ++m) acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[r], xf[m], acc[r][m], 0, 0, 0);
   };
 
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int st = 0; st < nst; ++st) {
-    if (st + 1 < nst) gload(st + 1);   // in flight while this stage is multiplied
-    compute(st & 1);
-    if (st + 1 < nst) lstore((st + 1) & 1);  // that buffer was last read in the previous iteration, before its barrier
-    __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TILE_NS - 1; ++i)
+    if (i < Kf) issue(i);
+  for (int st = 0; st < Kf; ++st) {
+    // This wave's loads of stage st have landed once at most the loads of the (up to two) later stages in flight
+    // are outstanding.  The barrier then says the same of every wave, and that every wave has finished reading
+    // the stage before st, whose ring slot the next loads overwrite.  It is a bare s_barrier between compiler
+    // fences: __syncthreads() would also wait for the loads of the later stages.  The LDS reads of compute()
+    // complete (lgkmcnt) before its MFMAs issue, so no wave reaches the next barrier with a read pending.
+    const int later = min(Kf - 1 - st, TILE_NS - 2);
+    wait_vmcnt_le(4 * later);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (st + TILE_NS - 1 < Kf) issue(st + TILE_NS - 1);
+    compute(st % TILE_NS);
   }
 
 #pragma unroll
@@ -519,9 +533,9 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 // Batched-prompt projections on 256 x 256 tiles.  Returns 0, or -1 when the shape does not tile (the caller then
 // uses bf16_gemm on row chunks).
 int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epi) {
-  if (a.rows <= 0 || a.rows % 256 || a.N % 256 || a.K % (32 * TILE_KC) || a.G < 1 || a.G > 4) return -1;
+  if (a.rows <= 0 || a.rows % 256 || a.N % 256 || a.K % 32 || a.G < 1 || a.G > 4) return -1;
   const dim3 grid(a.N / 256, a.rows / 256), blk(512);
-  const size_t lds = (size_t)2 * TILE_KC * TILE_FR * 64 * sizeof(bf16x8);  // 128 KiB of the CU's 160
+  const size_t lds = (size_t)TILE_NS * TILE_FR * 64 * sizeof(bf16x8);  // 128 KiB of the CU's 160
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute((const void *)k_gemm_tile<EPI_QKV_ROWS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
