@@ -98,7 +98,7 @@ struct GemmArgs {
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U, int waves);
 int bf16_gemm_groups(int N, int R);
 // Batched prompt only (a.rows > 0; EPI_QKV_ROWS, EPI_RESID or EPI_RELU): 256 x 256 output tiles with LDS-staged
-// operands.  Needs rows % 256 == 0, N % 256 == 0, K % 64 == 0; returns -1 otherwise (nothing launched).
+// operands.  Needs rows % 256 == 0 and N % 256 == 0 (K % 32 == 0 as everywhere); returns -1 otherwise (nothing launched).
 int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epilogue);
 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
