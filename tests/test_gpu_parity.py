@@ -487,3 +487,16 @@ def test_batched_prefill_matches_column_prefill():
         sl = slice(int(start[r]), P)                      # padded columns are never read: not compared
         np.testing.assert_allclose(ka[sl], kb[sl], rtol=2e-2, atol=2e-2)
         np.testing.assert_allclose(va[sl], vb[sl], rtol=2e-2, atol=2e-2)
+
+
+@pytest.mark.parametrize("f", [32, 64, 96, 288])
+def test_prompt_tiles_short_and_odd_k(f):
+    # the tiled prompt GEMM keeps a ring of k-steps in flight: FFN widths of 1, 2, 3 and 9 k-steps exercise a ring
+    # that never fills, fills exactly, and wraps at an odd count (FFN2 runs on the tile kernel with K = f; FFN1, whose
+    # N = f does not tile, falls back to the weight-streaming kernel)
+    shape = S.ModelShape(L=2, d=256, H=4, f=f, V=500, max_pos=64)
+    w = bf16_weights(shape, 61 + f)
+    B, P, N = 6, 33, 40
+    pr = S.make_prompts(B, P, shape.V, 62)
+    mask = S.make_ragged_mask(B, P, 7, P, seed=63)
+    compare(shape, w, pr, P, N, 1, 2, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, min_decided=0.0)
