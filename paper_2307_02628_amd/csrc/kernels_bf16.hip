@@ -185,7 +185,10 @@ template <int MB, int R, int EPI, int U, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
   constexpr int RM = R * MB;
   extern __shared__ floatx4 red[];  // [WAVES][RM][64 lanes]
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // The wave index is the same in all lanes.  Saying so makes the loop conditions that depend on it scalar: as
+  // (formally) divergent exits they make the compiler shuttle every accumulator between register files in each
+  // iteration to keep the values of lanes that might have left the loop.
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int Kf = a.K >> 5;
   // K range of this workgroup, cut into buffers of U k-steps that are dealt
   // round-robin to the waves: at any moment the workgroup reads WAVES * U KiB
@@ -248,19 +251,26 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
   if constexpr (EARLY) fetch_pre(0);
 
   // two register buffers: the loads of one are in flight while the MFMAs of the other issue
-  int j = wave;
-  if (j < nbuf) {
-    load(j, w0, x0);
-    while (true) {
-      const int j1 = j + WAVES, j2 = j + 2 * WAVES;
-      if (j1 < nbuf) load(j1, w1, x1);
-      fma(w0, x0);
-      if (j1 >= nbuf) break;
-      if (j2 < nbuf) load(j2, w0, x0);
-      fma(w1, x1);
-      if (j2 >= nbuf) break;
-      j = j2;
-    }
+  // A wave beyond the last buffer (short K) streams buffer 0 with its weights zeroed, once: guarding the loop instead
+  // makes the compiler keep two copies of the accumulators and move all of them between the copies every iteration.
+  const bool idle = wave >= nbuf;
+  int j = idle ? 0 : wave;
+  load(j, w0, x0);
+  if (idle) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < R; ++r) w0[u][r] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  while (true) {
+    const int j1 = j + WAVES, j2 = j + 2 * WAVES;
+    if (j1 < nbuf) load(j1, w1, x1);
+    fma(w0, x0);
+    if (j1 >= nbuf) break;
+    if (j2 < nbuf) load(j2, w0, x0);
+    fma(w1, x1);
+    if (j2 >= nbuf) break;
+    j = j2;
   }
 
   // sum the waves' partial tiles in a fixed order (deterministic).  The LDS buffer holds RS of the R tile rows
