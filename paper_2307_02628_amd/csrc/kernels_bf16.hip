@@ -676,7 +676,8 @@ __global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 wa
   constexpr int QC = DH / 32, VM = DH / 16;
   __shared__ float sm_m[NW], sm_l[NW], sm_dot[NW];
   __shared__ float sm_o[NW][DH];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4;
+  // uniform wave index: block numbers, page lookups and block addresses become scalar work
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, grp = lane >> 4;
   const int H = a.kv.H, h = blockIdx.x % H, d = H * DH;
   // longest rows are dispatched first, so that the last workgroups to start are the short ones
   const int b = a.order ? a.order[blockIdx.x / H] : (int)(blockIdx.x / H);
