@@ -500,3 +500,25 @@ def test_prompt_tiles_short_and_odd_k(f):
     pr = S.make_prompts(B, P, shape.V, 62)
     mask = S.make_ragged_mask(B, P, 7, P, seed=63)
     compare(shape, w, pr, P, N, 1, 2, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, min_decided=0.0)
+
+
+def test_batched_prefill_is_deterministic():
+    # the prompt pass (tile GEMM with its ring of in-flight operand stages, prompt attention, row kernels) has no
+    # atomics and a fixed summation order: three runs give bit-identical logits and cache contents
+    shape = MID
+    w = bf16_weights(shape, 71)
+    B, P, N = 9, 48, 52
+    pr = S.make_prompts(B, P, shape.V, 72)
+    mask = S.make_ragged_mask(B, P, 30, P, seed=73)
+    runs = []
+    for _ in range(3):
+        cfg = skd.make_config(shape, B, P, N, 1, 3, page_tokens=32)
+        with skd.Decoder(cfg, w) as dec:
+            dec.prefill(pr, mask)
+            lg = dec.logits_argmax()[1].copy()
+            kv = [dec.kv_read(l, b) for l in range(shape.L) for b in (0, B - 1)]
+            runs.append((lg, kv))
+    for lg, kv in runs[1:]:
+        assert np.array_equal(lg, runs[0][0])
+        for (k1, v1), (k0, v0) in zip(kv, runs[0][1]):
+            assert np.array_equal(k1, k0) and np.array_equal(v1, v0)
