@@ -168,7 +168,14 @@ int skd_prefill(skd_state *st, const int32_t *tokens, const uint8_t *attn_mask);
 int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_in);
 
 /* Final LayerNorm + LM head + greedy argmax on the hidden state of the last
- * processed column.  tokens_out [B] (may be NULL) receives, per row, the
+ * processed column: every column emits a token for the whole batch, whatever
+ * number of layers it ran (Section 2.1: one exit point per batch column; the
+ * hidden state that leaves the last active layer goes straight to the head,
+ * Section 2.4).  The paper leaves the head itself to the base model: the final
+ * LayerNorm and the LM head always run and the head is tied to the token
+ * embedding unless skd_weights.lm_head is given; the contract path is greedy
+ * (beam 1), with the LOWEST index winning ties, and Section 3.2's sampling
+ * setting is skd_logits_sample below.  tokens_out [B] (may be NULL) receives, per row, the
  * lowest index attaining the maximum logit; logits_out [B][vocab] fp32 (may be
  * NULL) receives the logits.  The tokens are also kept inside the state for
  * skd_decode_step(.., NULL).  Errors: SKD_ERR_NULL, SKD_ERR_ORDER (nothing

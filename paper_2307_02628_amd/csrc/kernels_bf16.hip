@@ -399,24 +399,40 @@ static void launch_gemm_r(hipStream_t s, const GemmArgs &a, int epi, int R, int 
 }
 
 // Batch tiles of 16 rows are compiled for B_pad in {16, 32, 64, 128}.
-int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves) {
+// Launch shape of a skinny GEMM, or false if the kernel cannot run it: nothing is launched here.
+static bool gemm_shape(const GemmArgs &a, int epi, int R, int &U, int waves, dim3 &grid, int &groups) {
   const int MB = a.B_pad / 16;
-  if (R < 1 || R > 4 || a.G < 1 || a.G > 4 || (waves != 4 && waves != 8) || MB < 1 || MB > 8) return -1;
+  if (R < 1 || R > 4 || a.G < 1 || a.G > 4 || (waves != 4 && waves != 8)) return false;
+  if (a.B_pad % 16 || (MB != 1 && MB != 2 && MB != 4 && MB != 8)) return false;
+  if (a.K < 32 || a.K % 32 || a.N < 1) return false;
   const int split = epi == EPI_LOGITS ? 1 : a.split;
   const int Kf = a.K / 32;
-  if (Kf % split) return -1;            // equal K ranges per workgroup
+  if (split < 1 || Kf % split) return false;  // equal K ranges per workgroup
   while (U > 1 && (Kf / split) % U) U >>= 1;  // whole buffers only
-  const int groups = bf16_gemm_groups(a.N, R);
+  if (U < 1) return false;
+  groups = bf16_gemm_groups(a.N, R);
   const bool by_rows = epi == EPI_QKV_ROWS || epi == EPI_RESID || (epi == EPI_RELU && a.rows > 0);
-  if ((epi == EPI_QKV_ROWS || epi == EPI_RESID) && (MB != 8 || a.rows <= 0)) return -1;
-  if (by_rows && (a.rows % a.B_pad || split != 1)) return -1;
-  const dim3 grid(groups, split, by_rows ? a.rows / a.B_pad : 1);
-  switch (MB) {
+  if ((epi == EPI_QKV_ROWS || epi == EPI_RESID) && (MB != 8 || a.rows <= 0)) return false;
+  if (by_rows && (a.rows % a.B_pad || split != 1)) return false;
+  grid = dim3(groups, split, by_rows ? a.rows / a.B_pad : 1);
+  return true;
+}
+
+int bf16_gemm_check(const GemmArgs &a, int epi, int R, int U, int waves) {
+  dim3 grid;
+  int groups = 0;
+  return gemm_shape(a, epi, R, U, waves, grid, groups) ? groups : -1;
+}
+
+int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves) {
+  dim3 grid;
+  int groups = 0;
+  if (!gemm_shape(a, epi, R, U, waves, grid, groups)) return -1;
+  switch (a.B_pad / 16) {
     case 1: launch_gemm_r<1>(s, a, epi, R, U, waves, grid); break;
     case 2: launch_gemm_r<2>(s, a, epi, R, U, waves, grid); break;
     case 4: launch_gemm_r<4>(s, a, epi, R, U, waves, grid); break;
-    case 8: launch_gemm_r<8>(s, a, epi, R, U, waves, grid); break;
-    default: return -1;
+    default: launch_gemm_r<8>(s, a, epi, R, U, waves, grid); break;
   }
   return groups;
 }
@@ -701,9 +717,12 @@ __global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 wa
 
   // Position t itself is not in the cache yet: its k and v arrive in the projection's staging rows.  Thread e
   // takes element e of q, k_t and v_t; the token joins the softmax as one more partial state when the waves
-  // are merged, and is filed into its page slot at the very end: nothing in this kernel reads that slot, and
-  // the lines around it have just been read, so the small stores hit lines that are resident in L2 (the same
-  // stores from the projection's epilogue or from a later kernel cost about 3 us per layer).
+  // are merged, and is filed into its page slot at the very end, when the lines around it have just been read
+  // and are resident in L2 (the same stores from the projection's epilogue or from a later kernel cost about
+  // 3 us per layer).  When len is not a multiple of 32 the 32-key block that contains slot len IS loaded above,
+  // with several splits possibly by another workgroup while this one stores: the result does not depend on
+  // what that load sees, because keys >= len get weight 0 and every slot of the pool holds finite bits at all
+  // times (the pool is zeroed when it is created and only finite k and v are ever filed), so 0 x slot = 0.
   const bool with_new = blockIdx.y == gridDim.y - 1 && len >= 0;
   float q_e = 0.f, k_e = 0.f, v_e = 0.f;
   bf16_t k_bits = 0, v_bits = 0;

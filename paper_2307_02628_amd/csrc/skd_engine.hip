@@ -93,6 +93,7 @@ struct skd_state {
   bf16_t *pf_a = nullptr, *pf_q = nullptr, *pf_o = nullptr, *pf_u = nullptr;
   int32_t *pf_seq = nullptr, *pf_first = nullptr;  // row map of the prompt pass (sequence of each row, first row of each sequence)
   int prefill_mode = 1;            // 1 = whole prompt per layer (bf16 path), 0 = column by column
+  int prefill_tiles = 1;           // 1 = prompt projections on 256 x 256 tiles where the shape allows
   // sequencing
   bool prefilled = false, have_hidden = false, have_argmax = false;
   int steps_done = 0;
@@ -350,7 +351,23 @@ const int32_t *bt_layer(const skd_state *st, int l) {
   return st->bt_dev + (size_t)l * st->cfg.batch * st->geom.max_pages;
 }
 
-// One column (all B rows at position t) through the given ascending layer list.
+// The four projections of a layer (the same shapes in every layer) against what the skinny GEMM can launch.
+bool decode_shapes_ok(const skd_state *st) {
+  const skd_config &c = st->cfg;
+  const int d = c.d_model, f = c.ffn;
+  GemmArgs ga{};
+  ga.B = c.batch; ga.B_pad = st->B_pad;
+  auto ok = [&](int N, int K, const GemmPlan &p, int epi) {
+    ga.N = N; ga.K = K; ga.G = p.R; ga.split = p.split;
+    return bf16_gemm_check(ga, epi, p.R, p.U, p.waves) > 0;
+  };
+  return ok(3 * d, d, st->p_qkv, EPI_QKV) && ok(d, d, st->p_out, EPI_PARTIAL) && ok(f, d, st->p_ffn1, EPI_RELU) &&
+         ok(d, f, st->p_ffn2, EPI_PARTIAL);
+}
+
+// One column (all B rows at position t) through the given ascending layer list.  Everything that can refuse
+// the column (layer list, cache lengths, launch shapes) is checked before the first launch, so an error leaves
+// the caches as they were.
 int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *layers, int n) {
   const skd_config &c = st->cfg;
   const int B = c.batch, d = c.d_model, f = c.ffn;
@@ -361,6 +378,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
     if (st->kv_len[l] != t) return SKD_ERR_ORDER;  // every earlier key of an active layer must exist
     if (t >= st->kv_cap[l]) return SKD_ERR_NOMEM;
   }
+  if (st->bf16 && !decode_shapes_ok(st)) return SKD_ERR_SHAPE;  // before the first launch: nothing is half done
   if (!st->bf16) {
     float *a = (float *)st->a, *qkv = (float *)st->q, *o = (float *)st->o, *u = (float *)st->u;
     { ProfScope ps_(st, SKD_PROF_OTHER); f32_embed(s, st->x, (const float *)st->tok_emb, (const float *)st->pos_emb, tokens_dev, st->start_dev, t, B, d, c.vocab); }
@@ -475,6 +493,8 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
     ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
   }
 
+  if (st->bf16 && !decode_shapes_ok(st)) return fail(SKD_ERR_SHAPE);  // an override the kernels cannot launch
+
   // ---- weights
   const size_t esz = w->elem == SKD_W_BF16 ? 2 : 4;
   size_t biggest = std::max({(size_t)V * d, (size_t)c.max_pos * d, (size_t)3 * d * d, (size_t)f * d});
@@ -516,6 +536,7 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   A(&st->x, (size_t)Bp * d);
   if (st->bf16) {
     st->prefill_mode = env_int("SKD_PREFILL_BATCHED", 1) != 0 ? 1 : 0;
+    st->prefill_tiles = env_int("SKD_PREFILL_TILES", 1) != 0 ? 1 : 0;
     st->max_split = std::max(st->p_out.split, st->p_ffn2.split);
     // split the key range of one head over several workgroups only when rows*heads alone cannot fill the chip
     // decode attention wants 16 waves on every CU: few (row, head) pairs get wider workgroups first (merged in
@@ -631,9 +652,8 @@ static int prefill_batched(skd_state *st, const int32_t *cols) {
   bf16_embed_ln_rows(s, cols, rm, (int)rows, (const bf16_t *)st->tok_emb, (const bf16_t *)st->pos_emb, st->lw[0].ln1_g,
                      st->lw[0].ln1_b, st->pf_x, st->pf_a, B, d, c.vocab);
   // 256 x 256 tiles where the shape allows, else 128-row chunks through the skinny kernel
-  static const int use_tiles = env_int("SKD_PREFILL_TILES", 1);
   auto proj = [&](const GemmArgs &g, int epi) {
-    if (use_tiles && bf16_gemm_tile(s, g, epi) == 0) return 0;
+    if (st->prefill_tiles && bf16_gemm_tile(s, g, epi) == 0) return 0;
     return bf16_gemm(s, g, epi, g.N % 64 ? 1 : 4, 1, 4);
   };
   for (int l = 0; l < L; ++l) {

@@ -96,6 +96,8 @@ struct GemmArgs {
 // waves in {4,8}: waves per workgroup.  K/32 must be a multiple of a.split.
 // Returns the number of row groups launched (grid.x), or -1 for an unsupported shape.
 int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U, int waves);
+// The same shape checks without a launch (only N, K, B_pad, G, split and rows of `a` are read): groups or -1.
+int bf16_gemm_check(const GemmArgs &a, int epilogue, int R, int U, int waves);
 int bf16_gemm_groups(int N, int R);
 // Batched prompt only (a.rows > 0; EPI_QKV_ROWS, EPI_RESID or EPI_RELU): 256 x 256 output tiles with LDS-staged
 // operands.  Needs rows % 256 == 0 and N % 256 == 0 (K % 32 == 0 as everywhere); returns -1 otherwise (nothing launched).

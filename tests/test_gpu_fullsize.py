@@ -89,3 +89,85 @@ def test_full_size_sampled_rows(name):
         decided = (srt[:, -1] - srt[:, -2]) > 4e-2 * rng
         np.testing.assert_array_equal(got[j][rows].argmax(-1)[decided], ref_tok[decided])
     ref_dec.close()
+
+
+def _prompt_grid(lens, N_out):
+    """(gx, gy) of the 256 x 256 tile launch the batched prompt pass makes for a projection with N_out outputs:
+    every sequence owns its real positions padded to whole 16-row tiles, the total padded to 256 rows."""
+    rows = sum((int(n) + 15) // 16 * 16 for n in lens)
+    rows_pad = (rows + 255) // 256 * 256
+    return N_out // 256, rows_pad // 256
+
+
+def _takes_xcd_order(gx, gy):
+    """The tile kernel deals its workgroups to the 8 XCDs in bands of 4 activation tiles only for such grids."""
+    return (gx * gy) % 8 == 0 and gy % 4 == 0
+
+
+PREFILL_WIDE = S.ModelShape(L=2, d=4096, H=32, f=16384, V=50272, max_pos=320)   # OPT-6.7B widths, two layers
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("ragged", [False, True])
+def test_batched_prefill_full_width(ragged):
+    # Section 2.3: the prompt runs through the full network, batched over positions.  At the benchmark's widths the
+    # prompt projections take the 256 x 256 tile kernel in its XCD-aware tile order with 128 (K = d) and 512
+    # (K = ffn) k-steps through the LDS ring, LayerNorm on 16-row tiles of 16 chunks, and prompt attention over 8
+    # key blocks.  The HIP path processes all sequences; the oracle recomputes sampled ones column by column (rows
+    # never interact).  Every cached key and value of the sampled sequences and the logits are compared, then two
+    # decode steps continue from the cache the prompt pass filled.
+    shape = PREFILL_WIDE
+    P, T = 256, 2
+    N = P + T
+    if ragged:
+        lens = [256, 199, 130, 256, 97, 33]
+        rows = [1, 4]
+    else:
+        lens = [256] * 4
+        rows = [2]
+    B = len(lens)
+    mask = np.zeros((B, P), dtype=np.uint8)
+    for b, n in enumerate(lens):
+        mask[b, P - n:] = 1
+    for n_out in (3 * shape.d, shape.d, shape.f):
+        gx, gy = _prompt_grid(lens, n_out)
+        assert gy == 4 and _takes_xcd_order(gx, gy), (n_out, gx, gy)
+    w = S.weights_to_bf16_values(S.make_weights(shape, seed=31))
+    pr = S.make_prompts(B, P, shape.V, 32)
+    tape = S.make_token_tape(B, T, shape.V, 33)
+    cfg = skd.make_config(shape, B, P, N, 1, 2, dtype=skd.BF16)
+    sets = [skd.skd_active_layers(P + j, cfg) for j in range(T)]
+
+    got_lg, got_kv = [], {}
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr, mask if ragged else None)
+        assert [dec.kv_len(l) for l in range(shape.L)] == [P] * shape.L
+        got_lg.append(dec.logits_argmax()[1])
+        for l in range(shape.L):
+            for b in rows:
+                got_kv[(l, b)] = dec.kv_read(l, b)
+        for j in range(T):
+            dec.decode_step(P + j, tape[j])
+            got_lg.append(dec.logits_argmax()[1])
+
+    ref = O.Decoder(shape, w, len(rows), N)
+    for i in range(P):
+        lg, _ = ref.column(i, pr[rows, i], list(range(shape.L)), mask[rows, i] if ragged else None,
+                           want_logits=(i == P - 1))
+    ref_lg = [lg]
+    for l in range(shape.L):
+        for r, b in enumerate(rows):
+            Ko, Vo = ref.kv_read(l, r)
+            K, V = got_kv[(l, b)]
+            sl = slice(P - lens[b], P)                       # padded columns are never read: not compared
+            scale = max(np.abs(Ko[sl]).max(), np.abs(Vo[sl]).max())
+            ek, ev = np.abs(K[sl] - Ko[sl]).max() / scale, np.abs(V[sl] - Vo[sl]).max() / scale
+            print(f"prefill full width ragged={ragged} layer {l} row {b}: K {ek:.2e} V {ev:.2e} of the value range")
+            assert ek <= 2e-2 and ev <= 2e-2, (l, b)
+    for j in range(T):
+        ref_lg.append(ref.column(P + j, tape[j][rows], sets[j])[0])
+    ref.close()
+    for j, (g, r) in enumerate(zip(got_lg, ref_lg)):
+        err = np.abs(g[rows] - r).max() / (r.max() - r.min())
+        print(f"prefill full width ragged={ragged} logits after column {P - 1 + j}: {err:.3e}")
+        assert err <= 2e-2

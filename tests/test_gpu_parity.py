@@ -368,6 +368,36 @@ def test_kv_page_contents_match_oracle(shape, batched):
         odec.close()
 
 
+def test_prompt_tiles_in_xcd_order_page_contents():
+    # 1024 prompt rows (16 sequences x 64 positions) at d = 512, ffn = 1536: the tiled prompt GEMM launches
+    # 6 x 4 (q,k,v and FFN1) and 2 x 4 (output projection, FFN2) workgroups, i.e. grids whose size is a multiple
+    # of 8 with 4 activation tiles, which it walks in its XCD-aware order.  Logits per step and every cached key
+    # and value against the oracle.
+    shape = MID
+    B, P, N = 16, 64, 70
+    for n_out in (3 * shape.d, shape.d, shape.f):
+        gx, gy = n_out // 256, (B * P) // 256
+        assert n_out % 256 == 0 and (gx * gy) % 8 == 0 and gy % 4 == 0
+    w = bf16_weights(shape, 81)
+    pr = S.make_prompts(B, P, shape.V, 82)
+    tape = S.make_token_tape(B, N - P, shape.V, 83)
+    compare(shape, w, pr, P, N, 1, 3, BF16_TOL, dtype=skd.BF16, page_tokens=32, tape=tape)
+    odec = O.Decoder(shape, w, B, N)
+    for i in range(P):
+        odec.column(i, pr[:, i], list(range(shape.L)), want_logits=False)
+    cfg = skd.make_config(shape, B, P, N, 1, 3, page_tokens=32)
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        for l in range(shape.L):
+            assert dec.kv_len(l) == odec.kv_len(l) == P
+            for b in range(B):
+                K, V = dec.kv_read(l, b)
+                Ko, Vo = odec.kv_read(l, b)
+                scale = max(np.abs(Ko).max(), np.abs(Vo).max())
+                assert np.abs(K - Ko).max() <= 2e-2 * scale and np.abs(V - Vo).max() <= 2e-2 * scale, (l, b)
+    odec.close()
+
+
 @pytest.mark.parametrize("env", [
     {"SKD_R_QKV": "1", "SKD_R_FFN1": "2", "SKD_R_HEAD": "3", "SKD_R_OUT": "1", "SKD_R_FFN2": "2"},
     {"SKD_U_QKV": "2", "SKD_U_FFN1": "4", "SKD_U_HEAD": "2", "SKD_U_OUT": "2", "SKD_U_FFN2": "4"},
@@ -396,6 +426,47 @@ def test_launch_shape_overrides(env):
                 os.environ.pop(k, None)
             else:
                 os.environ[k] = v
+
+
+@pytest.mark.parametrize("dtype", [skd.FP32, skd.BF16])
+@pytest.mark.parametrize("far", [False, True])
+def test_argmax_exact_ties_take_lowest_index(dtype, far):
+    # greedy head: the LOWEST index attaining the maximum.  An untied LM head with duplicated rows makes every
+    # logit tie exactly with its twin: 500 rows away (another workgroup of the LM-head projection, merged by the
+    # final reduction) or in the next row (same 16-row tile, merged inside the projection's epilogue).
+    shape = S.TINY
+    w = S.make_weights(shape, 0)
+    lm = np.array(w["tok_emb"], copy=True)
+    if far:
+        lm[shape.V // 2:] = lm[:shape.V // 2]
+    else:
+        lm[1::2] = lm[0::2]
+    w["lm_head"] = lm
+    if dtype == skd.BF16:
+        w = S.weights_to_bf16_values(w)
+    B, P, N = 5, 6, 12
+    pr = S.make_prompts(B, P, shape.V, 44)
+    tape = S.make_token_tape(B, N - P, shape.V, 45)
+    cfg = skd.make_config(shape, B, P, N, 2, 4, dtype=dtype)
+    odec = O.Decoder(shape, w, B, N)
+    for i in range(P):
+        _, otok = odec.column(i, pr[:, i], list(range(shape.L)), want_logits=(i == P - 1))
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        for k in range(N - P + 1):
+            tok, lg = dec.logits_argmax()
+            twin = tok + shape.V // 2 if far else tok + 1
+            assert (tok < shape.V // 2).all() if far else (tok % 2 == 0).all()
+            rows = np.arange(B)
+            np.testing.assert_array_equal(lg[rows, tok], lg[rows, twin])        # the tie is exact
+            np.testing.assert_array_equal(lg[rows, tok], lg.max(axis=1))
+            np.testing.assert_array_equal(tok, lg.argmax(axis=1))
+            assert (otok < shape.V // 2).all() if far else (otok % 2 == 0).all()  # the oracle breaks ties the same way
+            if k == N - P:
+                break
+            dec.decode_step(P + k, tape[k])
+            _, otok = odec.column(P + k, tape[k], O.active_layers(P + k, P, N, 2, 4, 0, shape.L))
+    odec.close()
 
 
 def test_vocabulary_above_sampler_limit():
