@@ -7,7 +7,11 @@ skd_logits_argmax (final LayerNorm, LM head, argmax), with inputs and outputs
 resident in HBM.  The default workload is the OPT-6.7B-shaped configuration
 (batch 32, prompt 512, 256 decode steps, layers 32 -> 6), timed with the
 SkipDecode schedule and again at full depth (n(t) = L) for the realised
-speedup.  Prints ONE JSON line.
+speedup.  With --steps K < T the K timed steps are spread evenly over the
+generation (each one timed in place during a pass over all T steps), so the
+timed sample has the schedule's mean depth; both legs are repeated and the
+median is reported.  The other full-size contract workloads are measured the
+same way and reported under "other_workloads".  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -48,6 +52,8 @@ for _x, (_w, _lo, _hi) in TABLE2["opt6.7b"].items():   # the paper's presets at 
 for _x, (_w, _lo, _hi) in TABLE2["opt1.3b"].items():
     WORKLOADS[f"opt1.3b_b16_p256_t256_table2-{_x}x"] = (S.OPT_1_3B, 16, 256, 256, _lo, _hi, None, _w)
 DEFAULT_WORKLOAD = "opt6.7b_b32_p512_t256_32to6"
+# the other full-size contract workloads, reported beside the default one
+OTHER_WORKLOADS = ("opt1.3b_b16_p256_t256_24to12", "opt6.7b_b8_p2048_t512_32to12", "opt6.7b_b128_p64-512_t128_24to8")
 
 
 def device_weights(shape, seed=0):
@@ -83,9 +89,24 @@ def class_bytes(shape, cls, sum_len):
             "lm_head": 2 * V * d, "attention": 2 * 2 * d * sum_len}.get(cls, 0)
 
 
-def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, profile, page_tokens=0,
-                   warmup_layers=0, head="argmax"):
-    """Create a state, prefill, warm up, rewind, time `steps` decode steps.  Returns timing dict."""
+def sample_positions(T, steps):
+    """Decode steps that are timed.  All of them when steps >= T; otherwise `steps` positions spread evenly over the
+    generation (the mid-points of `steps` equal strata), so that the sample's mean number of active layers and mean
+    KV length are those of the whole schedule and not those of its first steps."""
+    if steps >= T:
+        return list(range(T))
+    return [int((j + 0.5) * T / steps) for j in range(steps)]
+
+
+def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, reps, profile, page_tokens=0,
+                   warmup_layers=0, head="argmax", contiguous=False):
+    """One leg (one schedule) of a workload: create a state, prefill, run the WHOLE generation once untimed (warm-up
+    that also covers every launch shape), then `reps` timed repetitions.  A repetition is one more pass over the
+    generation from position P in which the sampled steps (sample_positions) are each bracketed by two events on
+    the library's stream: every timed step runs in its real context (cache contents, preceding step).  With
+    steps >= T the whole pass sits between one pair of events instead.  `contiguous`: no untimed pass, the first
+    `steps` steps are timed in one bracket after `warmup` warm-up steps (bounded dispatch count, for counter runs).
+    Returns per-repetition times and the byte accounting of the timed steps."""
     N = P + T
     stream = torch.cuda.Stream()
     cfg = skd.make_config(shape, B, P, N, n_min, n_max, warmup_layers, dtype=skd.BF16, io_on_device=1,
@@ -115,57 +136,183 @@ def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, war
             else:
                 dec.logits_argmax_device(toks, None)
 
-    run(0, min(warmup, T))
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    if contiguous:
+        ks = list(range(min(steps, T)))
+        run(0, min(warmup, T))
+    else:
+        ks = sample_positions(T, steps)
+        run(0, T)                                   # untimed: the whole generation (>= `warmup` steps)
     dec.synchronize()
-    dec.rewind(P)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    ev0.record(stream)
-    run(0, steps)
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    ms = ev0.elapsed_time(ev1)
-    out = {"ms": ms, "prefill_s": prefill_s, "layers": layers[:steps], "sum_len": sum_len[:steps],
-           "bytes": sum(step_bytes(shape, layers[k], sum_len[k]) for k in range(steps)),
+    whole = contiguous or len(ks) == T
+    last = ks[-1] + 1 if contiguous else T
+    rep_ms, first_ms = [], []
+    for _ in range(reps):
+        dec.rewind(P)
+        torch.cuda.synchronize()
+        if whole:
+            e0, e1, f1 = ev(), ev(), ev()
+            e0.record(stream)
+            run(0, 1)
+            f1.record(stream)
+            run(1, last)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            rep_ms.append(e0.elapsed_time(e1))
+            first_ms.append(e0.elapsed_time(f1))
+        else:
+            pairs, nxt = [], 0
+            for k in sorted(set(ks) | {0}):
+                run(nxt, k)
+                a, b = ev(), ev()
+                a.record(stream)
+                run(k, k + 1)
+                b.record(stream)
+                pairs.append((k, a, b))
+                nxt = k + 1
+            run(nxt, T)
+            torch.cuda.synchronize()
+            t = {k: a.elapsed_time(b) for k, a, b in pairs}
+            rep_ms.append(sum(t[k] for k in ks))
+            first_ms.append(t[0])
+    out = {"rep_ms": rep_ms, "first_step_ms": first_ms, "prefill_s": prefill_s, "ks": ks,
+           "layers": [layers[k] for k in ks], "sum_len": [sum_len[k] for k in ks],
+           "bytes": sum(step_bytes(shape, layers[k], sum_len[k]) for k in ks),
            "kv_pages": dec.kv_pages()}
     if profile:
-        # the same timed region four more times (the line's `value` stays the first, contract-defined one)
-        reps = [ms]
-        for _ in range(4):
+        # kernel durations over the whole generation: every launch gets its own pair of events, stamped with the
+        # kernel's begin and end (skd_profile_enable mode 1); then once more with event brackets around the
+        # launches of each class on the stream (mode 2), which adds the cost of the two markers to every figure
+        span = range(last)
+        for mode, key in ((1, "profile"), (2, "profile_bracketed")):
             dec.rewind(P)
-            torch.cuda.synchronize()
-            ev0.record(stream)
-            run(0, steps)
-            ev1.record(stream)
-            torch.cuda.synchronize()
-            reps.append(ev0.elapsed_time(ev1))
-        out["repeat_ms"] = reps
+            dec.profile_enable(mode)
+            run(0, last)
+            prof = dec.profile_read()
+            dec.profile_enable(0)
+            for cls, rec in prof.items():
+                if cls == "attention":
+                    rec["bytes"] = sum(layers[k] * class_bytes(shape, cls, sum_len[k]) for k in span)
+                elif cls == "lm_head":
+                    rec["bytes"] = len(span) * class_bytes(shape, cls, 0)
+                else:
+                    rec["bytes"] = sum(layers[k] for k in span) * class_bytes(shape, cls, 0)
+            out[key] = prof
+        # step time against the number of active layers: one event pair per step of a whole pass
         dec.rewind(P)
-        dec.profile_enable(True)
-        run(0, steps)
-        prof = dec.profile_read()
-        dec.profile_enable(False)
-        for cls, rec in prof.items():
-            if cls == "attention":
-                rec["bytes"] = sum(layers[k] * class_bytes(shape, cls, sum_len[k]) for k in range(steps))
-            elif cls == "lm_head":
-                rec["bytes"] = steps * class_bytes(shape, cls, 0)
-            else:
-                rec["bytes"] = sum(layers[:steps]) * class_bytes(shape, cls, 0)
-        out["profile"] = prof
-        # step time against the number of active layers: one event pair per step
-        dec.rewind(P)
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        evs = [ev() for _ in range(last + 1)]
         evs[0].record(stream)
-        for k in range(steps):
+        for k in range(last):
             run(k, k + 1)
             evs[k + 1].record(stream)
         torch.cuda.synchronize()
-        out["step_ms"] = [evs[k].elapsed_time(evs[k + 1]) for k in range(steps)]
+        out["step_ms"] = [evs[k].elapsed_time(evs[k + 1]) for k in range(last)]
+        out["step_layers"] = layers[:last]
     dec.close()
     del dec
     torch.cuda.synchronize()
     return out
+
+
+def traffic_ratio(workload, kernel):
+    """HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size) over algorithmic
+    bytes per launch, as stored by the counter runs described in profiles/pmc_traffic_*.md.  None if that workload
+    or kernel has not been measured."""
+    path = os.path.join(ROOT, "profiles", "traffic_ratios.json")
+    if not os.path.exists(path):
+        return None
+    return json.load(open(path)).get(workload, {}).get("kernels", {}).get(kernel, {}).get("ratio")
+
+
+def measure_workload(skd, torch, name, w, steps, warmup, reps, profile, args):
+    """Skip leg and full-depth leg of one workload; returns the figures of the bench line."""
+    shape, B, P, T, n_min, n_max, ragged, *rest = WORKLOADS[name]
+    wl = rest[0] if rest else 0
+    steps = min(steps if steps > 0 else T, T)
+    mask = S.make_ragged_mask(B, P, ragged[0], ragged[1], seed=2) if ragged else None
+    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, warmup, reps, profile,
+                          args.page_tokens, wl, args.head, args.contiguous)
+    full = None
+    if not args.no_full_depth:
+        full = run_generation(skd, torch, shape, w, B, P, T, shape.L, shape.L, mask, steps, warmup, reps, False,
+                              args.page_tokens, 0, args.head, args.contiguous)
+    n_timed = len(skip["ks"])
+    ms = float(np.median(skip["rep_ms"]))
+    tok_s = B * n_timed / (ms * 1e-3)
+    gbs = skip["bytes"] / (ms * 1e-3) / 1e9
+    r = np.array(skip["rep_ms"], dtype=np.float64) / n_timed
+    res = {
+        "value": tok_s, "unit": "tokens/s", "steps": n_timed, "ms_per_step": ms / n_timed,
+        "config": {"workload": name, "batch": B, "prompt": P, "decode_steps": T,
+                   "schedule": f"linear {n_max}->{n_min} of {shape.L} layers" + (f", {wl} warm-up" if wl else ""),
+                   "timed_steps": ("the first %d steps" % n_timed) if args.contiguous else
+                                  ("all %d steps" % T) if n_timed == T else
+                                  (f"{n_timed} of {T} steps, evenly spaced (k = {', '.join(map(str, skip['ks'][:2]))}, ..., "
+                                   f"{skip['ks'][-1]}), each timed inside a pass over the whole generation"),
+                   "sum_n": int(sum(skip["layers"])), "mean_n": float(np.mean(skip["layers"]))},
+        "hbm_gbs": gbs, "hbm_frac_of_8TBs": gbs / HBM_PEAK_GBS,
+        "algorithmic_gb_per_step": skip["bytes"] / n_timed / 1e9,
+        "prefill_s": skip["prefill_s"],
+        "kv_pages_reserved_vs_dense": list(skip["kv_pages"]),
+        "ms_per_step_repeats": {"n": int(r.size), "median": float(np.median(r)), "min": float(r.min()),
+                                "max": float(r.max())},
+    }
+    if full:
+        fms = float(np.median(full["rep_ms"]))
+        ftok = B * n_timed / (fms * 1e-3)
+        fr = np.array(full["rep_ms"], dtype=np.float64) / n_timed
+        res["full_depth"] = {"value": ftok, "unit": "tokens/s", "ms_per_step": fms / n_timed,
+                             "hbm_gbs": full["bytes"] / (fms * 1e-3) / 1e9,
+                             "ms_per_step_repeats": {"n": int(fr.size), "median": float(np.median(fr)),
+                                                     "min": float(fr.min()), "max": float(fr.max())}}
+        res["speedup_vs_full_depth"] = tok_s / ftok
+        res["ideal_layer_ratio"] = shape.L * n_timed / sum(skip["layers"])
+        res["ideal_byte_ratio"] = full["bytes"] / skip["bytes"]
+        if n_max == shape.L and wl == 0:
+            # step k = 0 runs all L layers over the same cache in both legs: the two legs on equal work
+            a, b = float(np.median(skip["first_step_ms"])), float(np.median(full["first_step_ms"]))
+            res["equal_depth_step_ms"] = {"skip_leg": a, "full_depth_leg": b, "ratio": b / a}
+    if "step_ms" in skip:
+        ns = np.array(skip["step_layers"], dtype=np.float64)
+        sm = np.array(skip["step_ms"], dtype=np.float64)
+        by_n = {int(n): round(float(sm[ns == n].mean()), 4) for n in sorted(set(ns.tolist()), reverse=True)}
+        fit = {}
+        if len(by_n) > 1:
+            slope, icpt = np.polyfit(ns, sm, 1)
+            resid = sm - (slope * ns + icpt)
+            fit = {"ms_per_active_layer": float(slope), "ms_fixed": float(icpt),
+                   "r2": float(1.0 - resid.var() / sm.var())}
+        res["step_ms_by_active_layers"] = by_n
+        res["step_ms_linear_fit"] = fit
+    roof = None
+    if "profile" in skip:
+        prof = {k: v for k, v in skip["profile"].items() if v["launches"]}
+        brk = skip["profile_bracketed"]
+        res["kernels"] = {k: {"avg_us": 1e3 * v["ms"] / v["launches"], "launches": v["launches"],
+                              "share": v["ms"] / sum(x["ms"] for x in prof.values()),
+                              "gbs": (v["bytes"] / (v["ms"] * 1e-3) / 1e9) if v["bytes"] else None,
+                              "avg_us_bracketed": 1e3 * brk[k]["ms"] / max(1, brk[k]["launches"])}
+                          for k, v in prof.items()}
+        dom = max((k for k in prof if prof[k]["bytes"]), key=lambda k: prof[k]["ms"])
+        ach = prof[dom]["bytes"] / (prof[dom]["ms"] * 1e-3) / 1e9
+        per_launch = prof[dom]["bytes"] / prof[dom]["launches"]
+        ratio = traffic_ratio(name, dom)
+        roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS,
+                "traffic": ratio * per_launch if ratio else None,
+                "traffic_source": ("HBM bytes / algorithmic bytes of this kernel on this workload as measured by "
+                                   "rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (profiles/traffic_ratios.json), times "
+                                   "the algorithmic bytes per launch of this run") if ratio else None,
+                "bytes_per_launch": per_launch,
+                "avg_launch_us": 1e3 * prof[dom]["ms"] / prof[dom]["launches"],
+                "launches": prof[dom]["launches"],
+                "duration": "begin/end time stamps of every launch of this kernel over all decode steps of the "
+                            "workload (HIP events attached to the launch), skip schedule",
+                "frac_with_event_brackets": brk[dom]["bytes"] / (brk[dom]["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    res["roofline"] = roof
+    return res
 
 
 def cpu_baseline(shape, B, P, T, n_min, n_max):
@@ -204,8 +351,17 @@ def cpu_baseline(shape, B, P, T, n_min, n_max):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (default: the workload's T)")
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=0,
+                    help="decode steps to time (default: the workload's T); fewer than T = that many steps spread "
+                         "evenly over the generation")
+    ap.add_argument("--warmup", type=int, default=8,
+                    help="untimed warm-up steps (the untimed pass over the whole generation always covers them)")
+    ap.add_argument("--reps", type=int, default=5, help="repetitions of the timed region (the line reports the median)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="only the named workload (default: the other contract workloads are measured as well)")
+    ap.add_argument("--contiguous", action="store_true",
+                    help="time the FIRST --steps steps in one bracket, with no pass over the whole generation "
+                         "(bounded number of launches: for hardware-counter runs)")
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--no-full-depth", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -252,80 +408,49 @@ def main():
     torch.cuda.empty_cache()
 
     shape, B, P, T, n_min, n_max, ragged, *rest = WORKLOADS[args.workload]
-    wl = rest[0] if rest else 0
-    steps = args.steps if args.steps > 0 else T
-    steps = min(steps, T)
-    mask = None
-    if ragged:
-        mask = S.make_ragged_mask(B, P, ragged[0], ragged[1], seed=2)
-    w = device_weights(shape, 0)
-    skip = run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, args.warmup, not args.no_profile, args.page_tokens, wl, args.head)
-    full = None
-    if not args.no_full_depth:
-        full = run_generation(skd, torch, shape, w, B, P, T, shape.L, shape.L, mask, steps, args.warmup, False, args.page_tokens)
-    del w
-    torch.cuda.empty_cache()
+    weights = {}
 
-    tok_s = B * steps / (skip["ms"] * 1e-3)
-    gbs = skip["bytes"] / (skip["ms"] * 1e-3) / 1e9
+    def weights_of(sh):
+        if sh not in weights:
+            weights.clear()              # one model's weights resident at a time
+            torch.cuda.empty_cache()
+            weights[sh] = device_weights(sh, 0)
+        return weights[sh]
+
+    m = measure_workload(skd, torch, args.workload, weights_of(shape), args.steps, args.warmup, args.reps,
+                         not args.no_profile, args)
     res = {
         "metric": "generated tokens/sec at OPT-6.7B shape, B=32, skip vs full depth; HBM GB/s",
-        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": skip["ms"] / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": m.pop("value"), "unit": m.pop("unit"), "n_gpus": 1, "steps": m.pop("steps"), "warmup": args.warmup,
+        "ms_per_step": m.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic", "head": args.head,
-        "config": {"workload": args.workload, "batch": B, "prompt": P, "decode_steps": T,
-                   "schedule": f"linear {n_max}->{n_min} of {shape.L} layers" + (f", {wl} warm-up" if wl else ""),
-                   "sum_n": int(sum(skip["layers"]))},
-        "hbm_gbs": gbs, "hbm_frac_of_8TBs": gbs / HBM_PEAK_GBS, "device_copy_read_plus_write_gbs": copy_gbs,
-        "algorithmic_gb_per_step": skip["bytes"] / steps / 1e9,
-        "prefill_s": skip["prefill_s"],
-        "kv_pages_reserved_vs_dense": list(skip["kv_pages"]),
+        "config": m.pop("config"), "device_copy_read_plus_write_gbs": copy_gbs,
     }
-    if full:
-        ftok = B * steps / (full["ms"] * 1e-3)
-        res["full_depth"] = {"value": ftok, "unit": "tokens/s", "ms_per_step": full["ms"] / steps,
-                             "hbm_gbs": full["bytes"] / (full["ms"] * 1e-3) / 1e9}
-        res["speedup_vs_full_depth"] = tok_s / ftok
-        res["ideal_layer_ratio"] = shape.L * steps / sum(skip["layers"])
-        res["ideal_byte_ratio"] = full["bytes"] / skip["bytes"]
-    if "repeat_ms" in skip:
-        r = np.array(skip["repeat_ms"], dtype=np.float64) / steps
-        res["ms_per_step_repeats"] = {"n": int(r.size), "median": float(np.median(r)), "min": float(r.min()),
-                                      "max": float(r.max())}
-    if "step_ms" in skip:
-        ns = np.array(skip["layers"], dtype=np.float64)
-        ms = np.array(skip["step_ms"], dtype=np.float64)
-        by_n = {int(n): round(float(ms[ns == n].mean()), 4) for n in sorted(set(ns.tolist()), reverse=True)}
-        fit = {}
-        if len(by_n) > 1:
-            slope, icpt = np.polyfit(ns, ms, 1)
-            resid = ms - (slope * ns + icpt)
-            fit = {"ms_per_active_layer": float(slope), "ms_fixed": float(icpt),
-                   "r2": float(1.0 - resid.var() / ms.var())}
-        res["step_ms_by_active_layers"] = by_n
-        res["step_ms_linear_fit"] = fit
-    roof = None
-    if "profile" in skip:
-        prof = {k: v for k, v in skip["profile"].items() if v["launches"]}
-        res["kernels"] = {k: {"avg_us": 1e3 * v["ms"] / v["launches"], "launches": v["launches"],
-                              "share": v["ms"] / sum(x["ms"] for x in prof.values()),
-                              "gbs": (v["bytes"] / (v["ms"] * 1e-3) / 1e9) if v["bytes"] else None}
-                          for k, v in prof.items()}
-        dom = max((k for k in prof if prof[k]["bytes"]), key=lambda k: prof[k]["ms"])
-        ach = prof[dom]["bytes"] / (prof[dom]["ms"] * 1e-3) / 1e9
-        # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE: the ratio to the algorithmic bytes was
-        # measured per kernel on a 2-layer slice with the same launch shapes (profiles/pmc_traffic_*.md)
-        traffic = None
-        tfile = os.path.join(ROOT, "profiles", "traffic_ratios_opt6.7b_b32.json")
-        if os.path.exists(tfile) and shape.d == 4096 and B == 32:
-            ratio = json.load(open(tfile))["kernels"].get(dom, {}).get("ratio")
-            if ratio:
-                traffic = ratio * prof[dom]["bytes"] / prof[dom]["launches"]
-        roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
-                "bytes_per_launch": prof[dom]["bytes"] / prof[dom]["launches"],
-                "avg_launch_us": 1e3 * prof[dom]["ms"] / prof[dom]["launches"]}
-    res["roofline"] = roof
+    res.update(m)
+    # the other contract workloads (same measurement, fewer repetitions, no per-class table): driver-visible figures
+    others = {}
+    if not args.no_other_workloads and args.workload == DEFAULT_WORKLOAD:
+        order = sorted(OTHER_WORKLOADS, key=lambda n: WORKLOADS[n][0] != shape)   # same-shape workloads first
+        for name in order:
+            o = measure_workload(skd, torch, name, weights_of(WORKLOADS[name][0]), args.steps, args.warmup,
+                                 max(3, args.reps // 2 + 1), not args.no_profile, args)
+            keep = ("value", "unit", "steps", "ms_per_step", "hbm_gbs", "hbm_frac_of_8TBs", "algorithmic_gb_per_step",
+                    "prefill_s", "speedup_vs_full_depth", "ideal_layer_ratio", "ideal_byte_ratio",
+                    "ms_per_step_repeats", "equal_depth_step_ms")
+            others[name] = {k: o[k] for k in keep if k in o}
+            others[name]["config"] = o["config"]
+            if "full_depth" in o:
+                others[name]["full_depth"] = {k: o["full_depth"][k] for k in ("value", "ms_per_step")}
+            if o.get("roofline"):
+                others[name]["roofline"] = {k: o["roofline"][k] for k in ("kernel", "achieved", "frac", "traffic",
+                                                                          "bytes_per_launch", "avg_launch_us")}
+            if "kernels" in o:
+                others[name]["kernels_gbs"] = {k: (round(v["gbs"], 1) if v["gbs"] else None)
+                                               for k, v in o["kernels"].items()}
+    weights.clear()
+    torch.cuda.empty_cache()
+    if others:
+        res["other_workloads"] = others
     res["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(shape, B, P, T, n_min, n_max)
     print(json.dumps(res))
 

@@ -244,13 +244,18 @@ int skd_debug_kv_load(skd_state *st, int32_t cols, const float *const *Kin, cons
  * stores nothing for them and returns zeros). */
 int skd_debug_kv_read(skd_state *st, int32_t layer, int32_t b, float *k_out, float *v_out);
 
-/* Per-kernel timing.  While enabled, every kernel launch of this state is
- * bracketed by two HIP events on the state's stream (this serialises nothing
- * but costs a little per launch, so time whole runs with it off).
+/* Per-kernel timing.  skd_profile_enable(st, 1): every kernel launch of this
+ * state is given its own pair of HIP events that receive the begin and end time
+ * stamps of that kernel (what a kernel trace reports as its duration); mode 2
+ * instead records one event before and one after the launches of each class
+ * on the state's stream, which adds the cost of the two markers to every
+ * measurement; 0 switches timing off.  Neither mode serialises anything, but
+ * both cost host time per launch, so time whole runs with timing off.
  * skd_profile_read waits for the stream and adds the elapsed milliseconds and
  * launch counts per kernel class into ms[SKD_PROF_CLASSES] and
  * launches[SKD_PROF_CLASSES] (either may be NULL), then clears the internal
- * accumulators.  Classes: see skd_prof_class. */
+ * accumulators.  Classes: see skd_prof_class.  Errors: SKD_ERR_NULL,
+ * SKD_ERR_RANGE (mode), SKD_ERR_HIP. */
 typedef enum {
   SKD_PROF_EMBED_LN = 0, /* embedding gather + first LayerNorm */
   SKD_PROF_GEMM_QKV = 1, /* q,k,v projection + KV page write  */

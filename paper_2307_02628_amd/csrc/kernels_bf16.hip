@@ -358,16 +358,16 @@ static void launch_gemm_epi(hipStream_t s, const GemmArgs &a, int epi, dim3 grid
   const size_t lds = (size_t)WAVES * gemm_stage_rows(WAVES, R, MB) * MB * 64 * sizeof(floatx4);
   const dim3 blk(WAVES * 64);
   switch (epi) {
-    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm<MB, R, EPI_PARTIAL, U, WAVES>), grid, blk, lds, s, a); break;
-    case EPI_QKV: hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV, U, WAVES>), grid, blk, lds, s, a); break;
-    case EPI_RELU: hipLaunchKernelGGL((k_gemm<MB, R, EPI_RELU, U, WAVES>), grid, blk, lds, s, a); break;
+    case EPI_PARTIAL: SKD_LAUNCH((k_gemm<MB, R, EPI_PARTIAL, U, WAVES>), grid, blk, lds, s, a); break;
+    case EPI_QKV: SKD_LAUNCH((k_gemm<MB, R, EPI_QKV, U, WAVES>), grid, blk, lds, s, a); break;
+    case EPI_RELU: SKD_LAUNCH((k_gemm<MB, R, EPI_RELU, U, WAVES>), grid, blk, lds, s, a); break;
     case EPI_QKV_ROWS:
-      if constexpr (MB == 8) hipLaunchKernelGGL((k_gemm<MB, R, EPI_QKV_ROWS, U, WAVES>), grid, blk, lds, s, a);
+      if constexpr (MB == 8) SKD_LAUNCH((k_gemm<MB, R, EPI_QKV_ROWS, U, WAVES>), grid, blk, lds, s, a);
       break;
     case EPI_RESID:
-      if constexpr (MB == 8) hipLaunchKernelGGL((k_gemm<MB, R, EPI_RESID, U, WAVES>), grid, blk, lds, s, a);
+      if constexpr (MB == 8) SKD_LAUNCH((k_gemm<MB, R, EPI_RESID, U, WAVES>), grid, blk, lds, s, a);
       break;
-    default: hipLaunchKernelGGL((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a); break;
+    default: SKD_LAUNCH((k_gemm<MB, R, EPI_LOGITS, U, WAVES>), grid, blk, lds, s, a); break;
   }
 }
 template <int MB, int R, int U>
@@ -571,9 +571,9 @@ int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epi) {
     configured = true;
   }
   switch (epi) {
-    case EPI_QKV_ROWS: hipLaunchKernelGGL(k_gemm_tile<EPI_QKV_ROWS>, grid, blk, lds, s, a); break;
-    case EPI_RESID: hipLaunchKernelGGL(k_gemm_tile<EPI_RESID>, grid, blk, lds, s, a); break;
-    case EPI_RELU: hipLaunchKernelGGL(k_gemm_tile<EPI_RELU>, grid, blk, lds, s, a); break;
+    case EPI_QKV_ROWS: SKD_LAUNCH(k_gemm_tile<EPI_QKV_ROWS>, grid, blk, lds, s, a); break;
+    case EPI_RESID: SKD_LAUNCH(k_gemm_tile<EPI_RESID>, grid, blk, lds, s, a); break;
+    case EPI_RELU: SKD_LAUNCH(k_gemm_tile<EPI_RELU>, grid, blk, lds, s, a); break;
     default: return -1;
   }
   return 0;
@@ -645,7 +645,7 @@ __global__ __launch_bounds__(1024) void k_embed_ln(const int32_t *tokens, const 
 void bf16_embed_ln(hipStream_t s, const int32_t *tokens, const int32_t *start, int t, const bf16_t *tok_emb,
                    const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
                    int V) {
-  hipLaunchKernelGGL(k_embed_ln, dim3(B), dim3(row_threads(d)), 0, s, tokens, start, t, tok_emb, pos_emb, g, b, x, a_out, d, V);
+  SKD_LAUNCH(k_embed_ln, dim3(B), dim3(row_threads(d)), 0, s, tokens, start, t, tok_emb, pos_emb, g, b, x, a_out, d, V);
 }
 
 // x[b][:] += bias + sum_s partial[s][b][:] (fixed order), then LayerNorm
@@ -675,7 +675,7 @@ __global__ __launch_bounds__(1024) void k_reduce_ln(const float *partial, int sp
 
 void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, const float *bias, float *x,
                     const float *g, const float *b, bf16_t *a_out, int B, int d) {
-  hipLaunchKernelGGL(k_reduce_ln, dim3(B), dim3(row_threads(d)), 0, s, partial, split, B_pad, bias, x, g, b, a_out, d);
+  SKD_LAUNCH(k_reduce_ln, dim3(B), dim3(row_threads(d)), 0, s, partial, split, B_pad, bias, x, g, b, a_out, d);
 }
 
 // ------------------------------------------------------------------ decode attention over the paged KV cache
@@ -895,17 +895,17 @@ void bf16_attention(hipStream_t s, const AttnArgs &a) {
   const dim3 grid(a.B * a.kv.H, a.splits);
   const int nw = a.waves >= 16 ? 16 : a.waves >= 8 ? 8 : a.waves >= 4 ? 4 : 2;
   if (a.kv.dh == 64) {
-    if (nw == 16) hipLaunchKernelGGL((k_attention<64, 16>), grid, dim3(1024), 0, s, a);
-    else if (nw == 8) hipLaunchKernelGGL((k_attention<64, 8>), grid, dim3(512), 0, s, a);
-    else if (nw == 2) hipLaunchKernelGGL((k_attention<64, 2>), grid, dim3(128), 0, s, a);
-    else hipLaunchKernelGGL((k_attention<64, 4>), grid, dim3(256), 0, s, a);
-    if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<64>, dim3(a.B * a.kv.H), dim3(64), 0, s, a);
+    if (nw == 16) SKD_LAUNCH((k_attention<64, 16>), grid, dim3(1024), 0, s, a);
+    else if (nw == 8) SKD_LAUNCH((k_attention<64, 8>), grid, dim3(512), 0, s, a);
+    else if (nw == 2) SKD_LAUNCH((k_attention<64, 2>), grid, dim3(128), 0, s, a);
+    else SKD_LAUNCH((k_attention<64, 4>), grid, dim3(256), 0, s, a);
+    if (a.splits > 1) SKD_LAUNCH(k_attn_merge<64>, dim3(a.B * a.kv.H), dim3(64), 0, s, a);
   } else {
-    if (nw == 16) hipLaunchKernelGGL((k_attention<128, 16>), grid, dim3(1024), 0, s, a);
-    else if (nw == 8) hipLaunchKernelGGL((k_attention<128, 8>), grid, dim3(512), 0, s, a);
-    else if (nw == 2) hipLaunchKernelGGL((k_attention<128, 2>), grid, dim3(128), 0, s, a);
-    else hipLaunchKernelGGL((k_attention<128, 4>), grid, dim3(256), 0, s, a);
-    if (a.splits > 1) hipLaunchKernelGGL(k_attn_merge<128>, dim3(a.B * a.kv.H), dim3(128), 0, s, a);
+    if (nw == 16) SKD_LAUNCH((k_attention<128, 16>), grid, dim3(1024), 0, s, a);
+    else if (nw == 8) SKD_LAUNCH((k_attention<128, 8>), grid, dim3(512), 0, s, a);
+    else if (nw == 2) SKD_LAUNCH((k_attention<128, 2>), grid, dim3(128), 0, s, a);
+    else SKD_LAUNCH((k_attention<128, 4>), grid, dim3(256), 0, s, a);
+    if (a.splits > 1) SKD_LAUNCH(k_attn_merge<128>, dim3(a.B * a.kv.H), dim3(128), 0, s, a);
   }
 }
 
@@ -1012,8 +1012,8 @@ __global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
 
 void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a) {
   const dim3 grid(a.kv.H, (a.rows + 63) / 64);
-  if (a.kv.dh == 64) hipLaunchKernelGGL(k_attention_rows<64>, grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(k_attention_rows<128>, grid, dim3(256), 0, s, a);
+  if (a.kv.dh == 64) SKD_LAUNCH(k_attention_rows<64>, grid, dim3(256), 0, s, a);
+  else SKD_LAUNCH(k_attention_rows<128>, grid, dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------ row kernels of the batched prompt
@@ -1110,17 +1110,17 @@ __global__ void k_gather_rows(const float *x_rows, float *x_out, RowMap rm, int 
 void bf16_embed_ln_rows(hipStream_t s, const int32_t *tokens, RowMap rm, int rows, const bf16_t *tok_emb,
                         const bf16_t *pos_emb, const float *g, const float *b, float *x, bf16_t *a_out, int B, int d,
                         int V) {
-  hipLaunchKernelGGL(k_embed_ln_rows, dim3(rows), dim3(1024), 0, s, tokens, rm, tok_emb, pos_emb, g, b, x, a_out, B, d, V);
+  SKD_LAUNCH(k_embed_ln_rows, dim3(rows), dim3(1024), 0, s, tokens, rm, tok_emb, pos_emb, g, b, x, a_out, B, d, V);
 }
 void bf16_ln_rows(hipStream_t s, const float *x, const float *g, const float *b, bf16_t *a_out, int rows, int d) {
   if (rows % 16 == 0 && d % 256 == 0 && d <= 256 * LNW_NC) {
-    hipLaunchKernelGGL(k_ln_rows16, dim3(rows / 16), dim3(1024), 0, s, x, g, b, a_out, d);
+    SKD_LAUNCH(k_ln_rows16, dim3(rows / 16), dim3(1024), 0, s, x, g, b, a_out, d);
     return;
   }
-  hipLaunchKernelGGL(k_ln_rows, dim3(rows), dim3(1024), 0, s, x, g, b, a_out, d);
+  SKD_LAUNCH(k_ln_rows, dim3(rows), dim3(1024), 0, s, x, g, b, a_out, d);
 }
 void bf16_gather_rows(hipStream_t s, const float *x_rows, float *x_out, RowMap rm, int B, int d) {
-  hipLaunchKernelGGL(k_gather_rows, dim3(B), dim3(256), 0, s, x_rows, x_out, rm, d);
+  SKD_LAUNCH(k_gather_rows, dim3(B), dim3(256), 0, s, x_rows, x_out, rm, d);
 }
 
 // ------------------------------------------------------------------ argmax over workgroup partials
@@ -1150,7 +1150,7 @@ __global__ void k_argmax_final(const float *pmax, const int32_t *pidx, int group
 }
 void bf16_argmax_final(hipStream_t s, const float *pmax, const int32_t *pidx, int groups, int B_pad, int32_t *tokens,
                        int B) {
-  hipLaunchKernelGGL(k_argmax_final, dim3(B), dim3(256), 0, s, pmax, pidx, groups, B_pad, tokens);
+  SKD_LAUNCH(k_argmax_final, dim3(B), dim3(256), 0, s, pmax, pidx, groups, B_pad, tokens);
 }
 
 // ------------------------------------------------------------------ weight preparation
@@ -1189,18 +1189,18 @@ void prep_matrix_frag(hipStream_t s, const void *src, int src_is_bf16, bf16_t *d
                       int G) {
   const long slots = (N_pad / 16) * (K / 32) * 64;
   const dim3 grid((unsigned)((slots + 255) / 256));
-  if (src_is_bf16) hipLaunchKernelGGL(k_prep_frag<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, N, K, N_pad, G);
-  else hipLaunchKernelGGL(k_prep_frag<float>, grid, dim3(256), 0, s, (const float *)src, dst, N, K, N_pad, G);
+  if (src_is_bf16) SKD_LAUNCH(k_prep_frag<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, N, K, N_pad, G);
+  else SKD_LAUNCH(k_prep_frag<float>, grid, dim3(256), 0, s, (const float *)src, dst, N, K, N_pad, G);
 }
 void prep_matrix_rm_bf16(hipStream_t s, const void *src, int src_is_bf16, bf16_t *dst, long n) {
   const dim3 grid((unsigned)((n + 255) / 256));
-  if (src_is_bf16) hipLaunchKernelGGL(k_prep_rm<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, n);
-  else hipLaunchKernelGGL(k_prep_rm<float>, grid, dim3(256), 0, s, (const float *)src, dst, n);
+  if (src_is_bf16) SKD_LAUNCH(k_prep_rm<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, n);
+  else SKD_LAUNCH(k_prep_rm<float>, grid, dim3(256), 0, s, (const float *)src, dst, n);
 }
 void prep_to_f32(hipStream_t s, const void *src, int src_is_bf16, float *dst, long n) {
   const dim3 grid((unsigned)((n + 255) / 256));
-  if (src_is_bf16) hipLaunchKernelGGL(k_prep_f32<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, n);
-  else hipLaunchKernelGGL(k_prep_f32<float>, grid, dim3(256), 0, s, (const float *)src, dst, n);
+  if (src_is_bf16) SKD_LAUNCH(k_prep_f32<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)src, dst, n);
+  else SKD_LAUNCH(k_prep_f32<float>, grid, dim3(256), 0, s, (const float *)src, dst, n);
 }
 
 // ------------------------------------------------------------------ KV debug hooks (bf16 pages)
@@ -1234,11 +1234,11 @@ __global__ void k_kv_read_bf16(const bf16_t *pool, const int32_t *bt_row, int st
 }
 void kv_load_bf16(hipStream_t s, const float *K, const float *V, bf16_t *pool, const int32_t *bt_layer,
                   const int32_t *start, int cols, int B, KvGeom g) {
-  if (cols > 0) hipLaunchKernelGGL(k_kv_load_bf16, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, start, cols, g);
+  if (cols > 0) SKD_LAUNCH(k_kv_load_bf16, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, start, cols, g);
 }
 void kv_read_bf16(hipStream_t s, const bf16_t *pool, const int32_t *bt_row, int start, int len, float *K, float *V,
                   KvGeom g) {
-  if (len > 0) hipLaunchKernelGGL(k_kv_read_bf16, dim3(len), dim3(256), 0, s, pool, bt_row, start, K, V, g);
+  if (len > 0) SKD_LAUNCH(k_kv_read_bf16, dim3(len), dim3(256), 0, s, pool, bt_row, start, K, V, g);
 }
 
 }  // namespace skd

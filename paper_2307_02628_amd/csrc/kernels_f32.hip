@@ -242,34 +242,34 @@ int sample_top_p(hipStream_t s, const float *logits, int B, int V, float tempera
   if (V > 1024 * SAMPLE_C) return -1;
   const int R = (V + 1023) / 1024;
   const float it = 1.0f / temperature;
-  if (R <= 16) hipLaunchKernelGGL(k_sample_top_p<16>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
-  else if (R <= 32) hipLaunchKernelGGL(k_sample_top_p<32>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
-  else if (R <= 52) hipLaunchKernelGGL(k_sample_top_p<52>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
-  else hipLaunchKernelGGL(k_sample_top_p<SAMPLE_C>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  if (R <= 16) SKD_LAUNCH(k_sample_top_p<16>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  else if (R <= 32) SKD_LAUNCH(k_sample_top_p<32>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  else if (R <= 52) SKD_LAUNCH(k_sample_top_p<52>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
+  else SKD_LAUNCH(k_sample_top_p<SAMPLE_C>, dim3(B), dim3(1024), 0, s, logits, V, it, top_p, u, tokens);
   return 0;
 }
 
 void f32_embed(hipStream_t s, float *x, const float *tok_emb, const float *pos_emb, const int32_t *tokens,
                const int32_t *start, int t, int B, int d, int V) {
-  hipLaunchKernelGGL(k_f32_embed, dim3(B), dim3(256), 0, s, x, tok_emb, pos_emb, tokens, start, t, d, V);
+  SKD_LAUNCH(k_f32_embed, dim3(B), dim3(256), 0, s, x, tok_emb, pos_emb, tokens, start, t, d, V);
 }
 void f32_layernorm(hipStream_t s, const float *x, const float *g, const float *b, float *out, int B, int d) {
-  hipLaunchKernelGGL(k_f32_layernorm, dim3(B), dim3(256), 0, s, x, g, b, out, d);
+  SKD_LAUNCH(k_f32_layernorm, dim3(B), dim3(256), 0, s, x, g, b, out, d);
 }
 void f32_linear(hipStream_t s, const float *W, const float *bias, const float *in, float *out, int B, int K, int N,
                 int relu, int accumulate) {
-  hipLaunchKernelGGL(k_f32_linear, dim3((N + 3) / 4, B), dim3(256), 0, s, W, bias, in, out, K, N, relu, accumulate);
+  SKD_LAUNCH(k_f32_linear, dim3((N + 3) / 4, B), dim3(256), 0, s, W, bias, in, out, K, N, relu, accumulate);
 }
 void f32_kv_write(hipStream_t s, const float *qkv, float *pool, const int32_t *bt_layer, int t, int B, KvGeom g) {
-  hipLaunchKernelGGL(k_f32_kv_write, dim3(B), dim3(256), 0, s, qkv, pool, bt_layer, t, g);
+  SKD_LAUNCH(k_f32_kv_write, dim3(B), dim3(256), 0, s, qkv, pool, bt_layer, t, g);
 }
 void f32_attention(hipStream_t s, const float *qkv, const float *pool, const int32_t *bt_layer, const int32_t *start,
                    int t, float *o, float *scores, int score_stride, int B, KvGeom g) {
-  hipLaunchKernelGGL(k_f32_attention, dim3(B * g.H), dim3(64), 0, s, qkv, pool, bt_layer, start, t, o, scores,
+  SKD_LAUNCH(k_f32_attention, dim3(B * g.H), dim3(64), 0, s, qkv, pool, bt_layer, start, t, o, scores,
                      score_stride, g);
 }
 void f32_argmax(hipStream_t s, const float *logits, int32_t *tokens, int B, int V) {
-  hipLaunchKernelGGL(k_f32_argmax, dim3(B), dim3(256), 0, s, logits, tokens, V);
+  SKD_LAUNCH(k_f32_argmax, dim3(B), dim3(256), 0, s, logits, tokens, V);
 }
 
 // ------------------------------------------------------------------ KV debug hooks (fp32 pages)
@@ -292,10 +292,10 @@ __global__ void k_kv_read_f32(const float *pool, const int32_t *bt_row, float *K
 }
 void kv_load_f32(hipStream_t s, const float *K, const float *V, float *pool, const int32_t *bt_layer, int cols, int B,
                  KvGeom g) {
-  if (cols > 0) hipLaunchKernelGGL(k_kv_load_f32, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, cols, g);
+  if (cols > 0) SKD_LAUNCH(k_kv_load_f32, dim3(cols, B), dim3(256), 0, s, K, V, pool, bt_layer, cols, g);
 }
 void kv_read_f32(hipStream_t s, const float *pool, const int32_t *bt_row, int len, float *K, float *V, KvGeom g) {
-  if (len > 0) hipLaunchKernelGGL(k_kv_read_f32, dim3(len), dim3(256), 0, s, pool, bt_row, K, V, g);
+  if (len > 0) SKD_LAUNCH(k_kv_read_f32, dim3(len), dim3(256), 0, s, pool, bt_row, K, V, g);
 }
 
 }  // namespace skd

@@ -46,6 +46,17 @@ struct GemmPlan {
 
 }  // namespace
 
+namespace skd {
+thread_local LaunchTimer *g_launch_timer = nullptr;
+}
+
+// hands the launches of one kernel class their event pairs (skd_profile_enable mode 1)
+struct StateTimer final : LaunchTimer {
+  skd_state *st = nullptr;
+  int cls = 0;
+  void next(hipEvent_t *start, hipEvent_t *stop) override;
+};
+
 struct skd_state {
   skd_config cfg{};
   hipStream_t stream = nullptr;
@@ -99,8 +110,9 @@ struct skd_state {
   int steps_done = 0;
   std::vector<int32_t> layers_tmp;
   std::vector<int32_t> n_table;    // caller-supplied layer counts per position (empty = the linear schedule)
-  // per-kernel timing (off by default)
-  bool profiling = false;
+  // per-kernel timing (off by default): 1 = each kernel's own begin/end time stamps, 2 = event brackets
+  int profiling = 0;
+  StateTimer timer;
   struct ProfRec { int cls; hipEvent_t a, b; };
   std::vector<ProfRec> prof_pending;
   std::vector<hipEvent_t> prof_free;
@@ -313,18 +325,24 @@ hipEvent_t prof_event(skd_state *st) {
   (void)hipEventCreate(&e);
   return e;
 }
-// brackets the launches issued inside its scope with two events when profiling is on
+// Times the launches issued inside its scope when profiling is on: mode 1 gives every launch its own event
+// pair, stamped with the kernel's begin and end; mode 2 records one event before and one after the launches.
 struct ProfScope {
   skd_state *st;
   int cls;
   hipEvent_t a = nullptr;
   ProfScope(skd_state *s, int c) : st(s), cls(c) {
-    if (st->profiling) {
+    if (st->profiling == 1) {
+      st->timer.st = st;
+      st->timer.cls = cls;
+      skd::g_launch_timer = &st->timer;
+    } else if (st->profiling == 2) {
       a = prof_event(st);
       if (a) (void)hipEventRecord(a, st->stream);
     }
   }
   ~ProfScope() {
+    skd::g_launch_timer = nullptr;
     if (a) {
       hipEvent_t b = prof_event(st);
       if (b) (void)hipEventRecord(b, st->stream);
@@ -332,6 +350,13 @@ struct ProfScope {
     }
   }
 };
+}  // namespace
+void StateTimer::next(hipEvent_t *start, hipEvent_t *stop) {
+  *start = prof_event(st);
+  *stop = prof_event(st);
+  st->prof_pending.push_back({cls, *start, *stop});
+}
+namespace {
 int prof_drain(skd_state *st) {
   HIPCHECK(hipStreamSynchronize(st->stream));
   for (auto &r : st->prof_pending) {
@@ -858,8 +883,9 @@ extern "C" int skd_rewind(skd_state *st, int32_t t) {
 
 extern "C" int skd_profile_enable(skd_state *st, int32_t on) {
   if (!st) return SKD_ERR_NULL;
+  if (on < 0 || on > 2) return SKD_ERR_RANGE;
   SKDCHECK(prof_drain(st));
-  st->profiling = on != 0;
+  st->profiling = on;
   return SKD_OK;
 }
 

@@ -2,11 +2,35 @@
 // Not part of the public ABI (include/skd.h is).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace skd {
 
 typedef uint16_t bf16_t;  // raw bfloat16 bit pattern in host-visible signatures
+
+// Per-launch timing.  While a thread has a LaunchTimer installed, every kernel launch it makes through
+// SKD_LAUNCH takes a (start, stop) event pair from the timer and goes through hipExtLaunchKernelGGL, which
+// stamps the two events with the begin and end of that kernel itself (the dispatch's own time stamps, what a
+// kernel trace reports), not with the time of extra marker packets around it.
+struct LaunchTimer {
+  virtual void next(hipEvent_t *start, hipEvent_t *stop) = 0;
+
+ protected:
+  ~LaunchTimer() = default;
+};
+extern thread_local LaunchTimer *g_launch_timer;
+
+#define SKD_LAUNCH(kernel, grid, blk, lds, stream, ...)                                        \
+  do {                                                                                         \
+    if (skd::g_launch_timer) {                                                                 \
+      hipEvent_t e0_ = nullptr, e1_ = nullptr;                                                 \
+      skd::g_launch_timer->next(&e0_, &e1_);                                                   \
+      hipExtLaunchKernelGGL(kernel, grid, blk, lds, stream, e0_, e1_, 0, __VA_ARGS__);         \
+    } else {                                                                                   \
+      hipLaunchKernelGGL(kernel, grid, blk, lds, stream, __VA_ARGS__);                         \
+    }                                                                                          \
+  } while (0)
 
 // Geometry of the paged KV cache.  A page holds `page_tokens` consecutive
 // positions of ONE batch row in ONE layer, all heads.  On the bf16 path a row's

@@ -244,8 +244,9 @@ class Decoder:
     def rewind(self, t: int):
         _check(self._lib.skd_rewind(self._h, t), "skd_rewind")
 
-    def profile_enable(self, on: bool):
-        _check(self._lib.skd_profile_enable(self._h, int(on)), "skd_profile_enable")
+    def profile_enable(self, mode):
+        """0 / False: off; 1 / True: each kernel's own begin and end time stamps; 2: event brackets on the stream."""
+        _check(self._lib.skd_profile_enable(self._h, int(mode)), "skd_profile_enable")
 
     def profile_read(self) -> Dict[str, Dict[str, float]]:
         ms = (C.c_double * len(PROF_CLASSES))()

@@ -63,3 +63,18 @@ def test_more_than_one_gpu_is_refused():
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+@pytest.mark.parametrize("name", ["opt6.7b_b32_p512_t256_32to6", "opt6.7b_b8_p2048_t512_32to12",
+                                  "opt1.3b_b16_p256_t256_24to12", "opt6.7b_b128_p64-512_t128_24to8"])
+@pytest.mark.parametrize("steps", [5, 20, 33])
+def test_timed_sample_has_the_schedules_mean_depth(name, steps):
+    # with fewer timed steps than the generation has, the timed positions are the mid-points of equal strata: strictly
+    # increasing, inside the generation, and their mean layer count is the schedule's (not that of its first steps)
+    shape, B, P, T, n_min, n_max, *_ = bench.WORKLOADS[name]
+    ks = bench.sample_positions(T, steps)
+    assert len(ks) == steps and ks == sorted(set(ks)) and 0 <= ks[0] and ks[-1] < T
+    n_all = [ORA.schedule(P + k, P, P + T, n_min, n_max, shape.L) for k in range(T)]
+    mean_all, mean_sample = np.mean(n_all), np.mean([n_all[k] for k in ks])
+    assert abs(mean_sample - mean_all) <= 0.02 * mean_all + 0.5 / steps * (n_max - n_min)
+    assert bench.sample_positions(T, T) == list(range(T)) == bench.sample_positions(T, T + 7)

@@ -381,7 +381,8 @@ def test_prompt_tiles_in_xcd_order_page_contents():
     w = bf16_weights(shape, 81)
     pr = S.make_prompts(B, P, shape.V, 82)
     tape = S.make_token_tape(B, N - P, shape.V, 83)
-    compare(shape, w, pr, P, N, 1, 3, BF16_TOL, dtype=skd.BF16, page_tokens=32, tape=tape)
+    compare(shape, w, pr, P, N, 1, 3, BF16_TOL, dtype=skd.BF16, page_tokens=32, tape=tape,
+            min_decided=0.0)   # near-flat logits at this width: the logit bar and the cache contents are the check
     odec = O.Decoder(shape, w, B, N)
     for i in range(P):
         odec.column(i, pr[:, i], list(range(shape.L)), want_logits=False)
