@@ -182,6 +182,27 @@ int skd_decode_step(skd_state *st, int32_t t, const int32_t *tokens_in);
  * processed yet), SKD_ERR_HIP. */
 int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logits_out);
 
+/* skd_logits_argmax for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same kernels and the same results, but the LM head's per-workgroup
+ * (max, argmax) partials live in a file-scope static device array of 2 MiB
+ * (every GPU the library runs on holds its own copy until the process ends)
+ * instead of buffers of the state, and the call itself calls no hipMalloc,
+ * hipFree or other allocating routine.  Only for states with dtype SKD_BF16
+ * and io_on_device = 1 (SKD_ERR_SHAPE otherwise): tokens_out [B] and
+ * logits_out [B][vocab] (either may be NULL) are device memory and the call
+ * only enqueues work on the state's stream.  Limit:
+ * ceil(vocab / (16 R)) * B_pad <= 262144 partials, R = LM-head tile rows per
+ * workgroup (2 below batch 32, else 4; SKD_R_HEAD), B_pad = batch padded to
+ * 16/32/64/128, i.e. vocabularies up to 131072 at batch 128 and larger ones
+ * at smaller batches; beyond the limit SKD_ERR_RANGE and nothing is launched.  All calls on one GPU, from whatever
+ * state, share that GPU's array: calls that may overlap there (different
+ * streams, different threads) race; calls on one stream are safe.  The array
+ * keeps the previous call's contents; nothing in it needs clearing, since the
+ * projection of a call writes every partial its final reduction reads.
+ * Errors otherwise as skd_logits_argmax. */
+int skd_logits_argmax_noalloc(skd_state *st, int32_t *tokens_out, float *logits_out);
+
 /* Sampling head (the paper's generation setting: temperature 0.3, top-p 0.7,
  * Section 3.2) in place of the greedy argmax: final LayerNorm + LM head, then
  * per row, with p_i = exp((z_i - max z) / temperature): the nucleus is the

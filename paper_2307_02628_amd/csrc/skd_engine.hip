@@ -31,7 +31,28 @@ extern "C" int skd_last_hip_error(void) { return g_last_hip; }
     if (r_ < 0) return r_;   \
   } while (0)
 
+// Scratch of skd_logits_argmax_noalloc: the per-workgroup (max, argmax) partials of the LM head, fp32 maxima in
+// the first half and int32 indices in the second.  Every GPU the library runs on holds its own copy of this
+// array at its own address until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress; kernels are given the resolved device address.
+#define SKD_NOALLOC_MAX_PARTIALS (1 << 18) /* workgroups of the LM head x padded batch rows */
+static __device__ __align__(256) unsigned char scratch[2 * 4 * SKD_NOALLOC_MAX_PARTIALS];  // 2 MiB
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, resolved once per device
+
+// Called with `device` current (skd_create): looks the array's address up on that device.
+int resolve_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return SKD_ERR_RANGE;
+  if (g_scratch_ptr[device]) return SKD_OK;
+  void *ptr = nullptr;
+  HIPCHECK(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+  if (!ptr) return SKD_ERR_HIP;
+  g_scratch_ptr[device] = ptr;
+  return SKD_OK;
+}
 
 struct LayerW {
   // matrices: fp32 row-major (debug path) or bf16 fragment-major (production path)
@@ -105,6 +126,7 @@ struct skd_state {
   int32_t *pf_seq = nullptr, *pf_first = nullptr;  // row map of the prompt pass (sequence of each row, first row of each sequence)
   int prefill_mode = 1;            // 1 = whole prompt per layer (bf16 path), 0 = column by column
   int prefill_tiles = 1;           // 1 = prompt projections on 256 x 256 tiles where the shape allows
+  int device = 0;                  // HIP device the state lives on
   // sequencing
   bool prefilled = false, have_hidden = false, have_argmax = false;
   int steps_done = 0;
@@ -519,6 +541,12 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
   }
 
   if (st->bf16 && !decode_shapes_ok(st)) return fail(SKD_ERR_SHAPE);  // an override the kernels cannot launch
+  {  // the device this state lives on, and that device's copy of the static scratch array
+    hipError_t e = hipGetDevice(&st->device);
+    if (e != hipSuccess) { g_last_hip = (int)e; return fail(SKD_ERR_HIP); }
+    const int src = resolve_scratch(st->device);
+    if (src != SKD_OK) return fail(src);
+  }
 
   // ---- weights
   const size_t esz = w->elem == SKD_W_BF16 ? 2 : 4;
@@ -832,6 +860,35 @@ extern "C" int skd_logits_argmax(skd_state *st, int32_t *tokens_out, float *logi
   if (logits_out)
     HIPCHECK(hipMemcpyAsync(logits_out, st->logits_dev, (size_t)B * V * sizeof(float), hipMemcpyDeviceToHost, s));
   HIPCHECK(hipStreamSynchronize(s));
+  return SKD_OK;
+}
+
+// skd_logits_argmax for callers that cannot allocate: same kernels, with the LM head's per-workgroup partials in
+// the static device array instead of the buffers skd_create reserved.  No hipMalloc / hipFree, no event creation,
+// no host-side staging: outputs are device memory and the call only enqueues work on the state's stream.
+extern "C" int skd_logits_argmax_noalloc(skd_state *st, int32_t *tokens_out, float *logits_out) {
+  if (!st) return SKD_ERR_NULL;
+  if (!st->have_hidden) return SKD_ERR_ORDER;
+  const skd_config &c = st->cfg;
+  if (!st->bf16 || !c.io_on_device) return SKD_ERR_SHAPE;
+  const int groups = bf16_gemm_groups(c.vocab, st->p_head.R);
+  if ((int64_t)groups * st->B_pad > SKD_NOALLOC_MAX_PARTIALS) return SKD_ERR_RANGE;  // beyond the static scratch
+  void *base = (st->device >= 0 && st->device < kMaxDevices) ? g_scratch_ptr[st->device] : nullptr;
+  if (!base) return SKD_ERR_ORDER;  // resolved by skd_create on the state's device
+  float *pmax = (float *)base;
+  int32_t *pidx = (int32_t *)((unsigned char *)base + 4 * (size_t)SKD_NOALLOC_MAX_PARTIALS);
+  hipStream_t s = st->stream;
+  GemmArgs ga{};
+  ga.B = c.batch; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.G = st->p_head.R; ga.A = (const bf16_t *)st->a;
+  ga.N = c.vocab; ga.K = c.d_model; ga.split = 1; ga.logits = logits_out; ga.pmax = pmax; ga.pidx = pidx;
+  if (bf16_gemm_check(ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves) != groups) return SKD_ERR_SHAPE;
+  // every partial the final reduction reads is written by the projection of this same call: nothing to clear
+  (void)bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves);
+  bf16_argmax_final(s, pmax, pidx, groups, st->B_pad, st->argmax_dev, c.batch);
+  HIPCHECK(hipGetLastError());
+  st->have_argmax = true;
+  if (tokens_out)
+    HIPCHECK(hipMemcpyAsync(tokens_out, st->argmax_dev, c.batch * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
   return SKD_OK;
 }
 

@@ -22,7 +22,7 @@ HOST, DEVICE = 0, 1
 W_FP32, W_BF16 = 0, 1
 
 EXPORTS = ["skd_schedule", "skd_active_layers", "skd_create", "skd_create_with_schedule", "skd_state_active_layers", "skd_prefill", "skd_decode_step",
-           "skd_logits_argmax", "skd_logits_sample", "skd_rewind", "skd_profile_enable", "skd_profile_read", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
+           "skd_logits_argmax", "skd_logits_argmax_noalloc", "skd_logits_sample", "skd_rewind", "skd_profile_enable", "skd_profile_read", "skd_kv_len", "skd_kv_pages_reserved", "skd_kv_pages_dense", "skd_synchronize",
            "skd_debug_read_hidden", "skd_debug_kv_load", "skd_debug_kv_read", "skd_destroy", "skd_strerror",
            "skd_last_hip_error"]
 
@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         l.skd_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         l.skd_logits_argmax.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        l.skd_logits_argmax_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.skd_logits_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         l.skd_rewind.argtypes = [C.c_void_p, C.c_int32]
         l.skd_profile_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -240,6 +241,10 @@ class Decoder:
     def logits_argmax_device(self, tokens_out=None, logits_out=None):
         """Device-I/O form: pointers / torch tensors on the device; asynchronous."""
         _check(self._lib.skd_logits_argmax(self._h, _ptr_of(tokens_out), _ptr_of(logits_out)), "skd_logits_argmax")
+
+    def logits_argmax_noalloc_rc(self, tokens_out=None, logits_out=None) -> int:
+        """skd_logits_argmax_noalloc (device I/O only): the return code, no exception."""
+        return self._lib.skd_logits_argmax_noalloc(self._h, _ptr_of(tokens_out), _ptr_of(logits_out))
 
     def rewind(self, t: int):
         _check(self._lib.skd_rewind(self._h, t), "skd_rewind")
