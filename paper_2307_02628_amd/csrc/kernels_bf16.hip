@@ -262,6 +262,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < R; ++r) w0[u][r] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
   }
+  // Behind the conditional prefetch the compiler cannot count the loads in flight and makes the first MFMA of a
+  // buffer wait for the prefetch as well, so a wave alone does not overlap its loads with its MFMAs: the other
+  // waves of the CU do.  Measured with the prefetch made unconditional (exact wait counts, twice the bytes in
+  // flight per wave): 2 % slower at 32 rows (8 waves per workgroup), faster only at 128 rows (4 waves).
   while (true) {
     const int j1 = j + WAVES, j2 = j + 2 * WAVES;
     if (j1 < nbuf) load(j1, w1, x1);
@@ -435,6 +439,256 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
     default: launch_gemm_r<8>(s, a, epi, R, U, waves, grid); break;
   }
   return groups;
+}
+
+// ------------------------------------------------------------------ skinny GEMM for 128 batch rows
+// With 8 batch tiles a workgroup pulls two bytes of activations out of L2 for every byte of weights it streams
+// from HBM, and on this part a CU's vector memory path serves the two kinds of request largely one after the
+// other: measured per CU with plain streaming waves, 512 KiB of HBM misses take 19.9 us and every further MiB of
+// L2 hits adds 7.5 us when separate waves fetch it (12.7 us when the same four waves fetch both in turn, as the
+// general kernel above does).  So the work is split by wave role:
+//   waves 0..3 (one per SIMD) stream the weights into registers, three k-steps deep, and issue the MFMAs;
+//   waves 4..7 fetch the activations with LDS-direct loads (no registers in flight) into a ring of four
+//   stages; a stage holds the 8 activation fragments of 4 consecutive k-steps; wave 4 + w fetches the k-step
+//   that wave w multiplies.  One bare s_barrier per stage orders the ring (as in the tiled prompt GEMM below).
+// With a.ws_rot the workgroups start their K range at different stages (and wrap), so that at any moment the
+// CUs of an XCD ask its L2 for different lines; the sum over k is then taken in that rotated order: fixed for a
+// given launch shape, hence run-to-run deterministic, but not the same order in every workgroup.
+constexpr int WS_NS = 4;  // ring stages
+constexpr int WS_CW = 4;  // MFMA waves = loader waves = k-steps per stage
+constexpr int WS_MB = 8;  // batch tiles
+
+template <int R, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_ws(GemmArgs a) {
+  constexpr int MB = WS_MB, NS = WS_NS;
+  constexpr int STAGE = WS_CW * MB * 64;     // bf16x8 units per stage (32 KiB)
+  extern __shared__ bf16x8 ws_lds[];         // ring [NS][WS_CW][MB][64 lanes]; later the reduction buffer
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int Kf = a.K >> 5;
+  const int kw0 = (int)((long)Kf * blockIdx.y / a.split), kw1 = (int)((long)Kf * (blockIdx.y + 1) / a.split);
+  const int nchunk = (kw1 - kw0) / WS_CW;  // the launcher makes this exact and >= 1
+  const int rot = a.ws_rot ? (int)((blockIdx.x >> 3) * 5u + blockIdx.y * 3u) % nchunk : 0;
+  floatx4 *red = (floatx4 *)ws_lds;        // [WS_CW][R * MB][64 lanes] after the main loop
+  auto bar = [&]() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  if (wave >= WS_CW) {
+    // ---- loader of k-step kw0 + 4 * chunk + l of every stage
+    const int l = wave - WS_CW;
+    const bf16x8 *Ab = (const bf16x8 *)a.A + act_lane(lane);  // fetched in MFMA lane order: LDS holds ready-made fragments
+    auto issue = [&](int ci) {
+      int c = ci + rot;
+      if (c >= nchunk) c -= nchunk;
+      const long kf = kw0 + c * WS_CW + l;
+      bf16x8 *dst = ws_lds + (ci % NS) * STAGE + l * (MB * 64);
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Ab + ((long)m * Kf + kf) * 64),
+                                         (__attribute__((address_space(3))) void *)(dst + m * 64), 16, 0, 0);
+    };
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+      if (i < nchunk) issue(i);
+    for (int ci = 0; ci < nchunk; ++ci) {
+      // this wave's 8 loads of stage ci have landed once only those of the (up to two) later stages in flight
+      // are outstanding (vector-memory operations of a wave complete in order)
+      const int later = min(nchunk - 1 - ci, NS - 2);
+      if (later == 0) __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt = 0
+      else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt <= 8
+      else __builtin_amdgcn_s_waitcnt(0x4F70);                  // vmcnt <= 16
+      bar();  // stage ci is complete; every wave has finished reading stage ci - 1
+      if (ci + NS - 1 < nchunk) issue(ci + NS - 1);  // into the slot of stage ci - 1
+    }
+    bar();  // every stage has been read: the ring becomes the reduction buffer
+  } else {
+    // ---- weight streamer + MFMA: k-step kw0 + 4 * chunk + wave of every stage
+    floatx4 acc[R][MB];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int m = 0; m < MB; ++m) acc[r][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const bf16x8 *Wl = (const bf16x8 *)a.W + lane;
+    long wbase[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int T = blockIdx.x * R + r;
+      wbase[r] = (((long)(T / a.G) * Kf + kw0 + wave) * a.G + T % a.G) * 64;
+    }
+    const long cstride = (long)a.G * 64 * WS_CW;  // one stage further along K
+    auto loadw = [&](int ci, bf16x8(&w)[R]) {
+      int c = ci + rot;
+      if (c >= nchunk) c -= nchunk;
+#pragma unroll
+      for (int r = 0; r < R; ++r) w[r] = __builtin_nontemporal_load(&Wl[wbase[r] + c * cstride]);
+    };
+    auto step = [&](int ci, bf16x8(&w)[R]) {
+      bar();
+      const bf16x8 *fs = ws_lds + (ci % NS) * STAGE + wave * (MB * 64) + lane;
+      bf16x8 x[MB];
+#pragma unroll
+      for (int m = 0; m < MB; ++m) x[m] = fs[m * 64];
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < MB; ++m) acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[r], x[m], acc[r][m], 0, 0, 0);
+    };
+    // three k-steps of weights in flight; the prefetches are unconditional (index clamped to the last stage,
+    // which is then fetched again and not used), so that the compiler can count the loads in flight, and fenced
+    // so that they stay ahead of the MFMAs they overlap with
+    bf16x8 w0[R], w1[R], w2[R];
+    const int cl = nchunk - 1;
+    loadw(0, w0);
+    loadw(min(1, cl), w1);
+    int ci = 0;
+    while (true) {
+      loadw(min(ci + 2, cl), w2);
+      __builtin_amdgcn_sched_barrier(0);
+      step(ci, w0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ci + 1 >= nchunk) break;
+      loadw(min(ci + 3, cl), w0);
+      __builtin_amdgcn_sched_barrier(0);
+      step(ci + 1, w1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ci + 2 >= nchunk) break;
+      loadw(min(ci + 4, cl), w1);
+      __builtin_amdgcn_sched_barrier(0);
+      step(ci + 2, w2);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ci + 3 >= nchunk) break;
+      ci += 3;
+    }
+    bar();  // all waves are done with the ring
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int m = 0; m < MB; ++m) red[(wave * (R * MB) + r * MB + m) * 64 + lane] = acc[r][m];
+  }
+
+  // ---- sum the four MFMA waves' tiles in a fixed order; all eight waves share the epilogue work
+  constexpr int NW = 2 * WS_CW;
+  constexpr int NP = (R * MB + NW - 1) / NW;
+  EpiPre pre[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int p = wave + i * NW;
+    if (p < R * MB) pre[i] = epi_prefetch<EPI>(a, (p % MB) * 16 + (lane & 15), (blockIdx.x * R + p / MB) * 16 + 4 * (lane >> 4));
+  }
+  __syncthreads();
+  float cand_v[NP];
+  int cand_i[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int p = wave + i * NW;
+    const int r = p / MB, m = p % MB;
+    if (p < R * MB) {
+      floatx4 v = red[p * 64 + lane];
+      for (int w = 1; w < WS_CW; ++w) v += red[(w * (R * MB) + p) * 64 + lane];
+      const int n0 = (blockIdx.x * R + r) * 16 + 4 * (lane >> 4);
+      if constexpr (EPI != EPI_LOGITS) {
+        gemm_epilogue<EPI>(a, m * 16 + (lane & 15), n0, v, pre[i]);
+      } else {
+        const int b = m * 16 + (lane & 15);
+        float best = -3.0e38f;
+        int bi = 0x7fffffff;
+        for (int j = 0; j < 4; ++j) {
+          if (n0 + j < a.N) {
+            if (a.logits && b < a.B) a.logits[(long)b * a.N + n0 + j] = v[j];
+            if (v[j] > best) { best = v[j]; bi = n0 + j; }
+          }
+        }
+        for (int o = 16; o < 64; o <<= 1) {
+          const float ov = __shfl_xor(best, o);
+          const int oi = __shfl_xor(bi, o);
+          if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        }
+        cand_v[i] = best;
+        cand_i[i] = bi;
+      }
+    }
+  }
+  if constexpr (EPI == EPI_LOGITS) {
+    __syncthreads();  // the reduction buffer is free: it now collects the candidates, [R * MB][16] values and indices
+    float *cv = (float *)ws_lds;
+    int *ci = (int *)ws_lds + R * MB * 16;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = wave + i * NW;
+      if (p < R * MB && lane < 16) {
+        cv[p * 16 + lane] = cand_v[i];
+        ci[p * 16 + lane] = cand_i[i];
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x < MB * 16) {
+      const int m = threadIdx.x >> 4, c = threadIdx.x & 15;
+      float best = cv[m * 16 + c];
+      int bi = ci[m * 16 + c];
+      for (int r = 1; r < R; ++r) {
+        const float ov = cv[(r * MB + m) * 16 + c];
+        const int oi = ci[(r * MB + m) * 16 + c];
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      a.pmax[(long)blockIdx.x * a.B_pad + m * 16 + c] = best;
+      a.pidx[(long)blockIdx.x * a.B_pad + m * 16 + c] = bi;
+    }
+  }
+}
+
+// Decode projections at 128 (padded) batch rows on the wave-specialised kernel.  Returns the number of row groups,
+// or -1 when the shape is not one it handles (the caller then uses bf16_gemm); nothing is launched in that case.
+static bool gemm_ws_shape(const GemmArgs &a, int epi, int R, dim3 &grid, int &groups) {
+  if (a.B_pad != 128 || a.rows != 0 || R < 1 || R > 4 || a.G < 1 || a.G > 4 || a.K < 32 || a.K % 32 || a.N < 1) return false;
+  if (epi != EPI_PARTIAL && epi != EPI_QKV && epi != EPI_RELU && epi != EPI_LOGITS) return false;
+  const int split = epi == EPI_LOGITS ? 1 : a.split;
+  const int Kf = a.K / 32;
+  if (split < 1 || Kf % split || (Kf / split) % WS_CW || Kf / split < WS_CW) return false;
+  groups = bf16_gemm_groups(a.N, R);
+  grid = dim3(groups, split, 1);
+  return true;
+}
+int bf16_gemm_ws_check(const GemmArgs &a, int epi, int R) {
+  dim3 grid;
+  int groups = 0;
+  return gemm_ws_shape(a, epi, R, grid, groups) ? groups : -1;
+}
+template <int R>
+static int launch_gemm_ws(hipStream_t s, const GemmArgs &a, int epi, dim3 grid) {
+  // the activation ring (4 stages of 32 KiB), reused for the cross-wave reduction (4 waves x R x 8 KiB): 128 KiB
+  constexpr size_t ring = (size_t)WS_NS * WS_CW * WS_MB * 64 * sizeof(bf16x8);
+  constexpr size_t redb = (size_t)WS_CW * R * WS_MB * 64 * sizeof(floatx4);
+  constexpr size_t lds = ring > redb ? ring : redb;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void *)k_gemm_ws<R, EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_gemm_ws<R, EPI_QKV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_gemm_ws<R, EPI_RELU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_gemm_ws<R, EPI_LOGITS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return -1;
+    configured = true;
+  }
+  const dim3 blk(512);
+  switch (epi) {
+    case EPI_PARTIAL: SKD_LAUNCH((k_gemm_ws<R, EPI_PARTIAL>), grid, blk, lds, s, a); break;
+    case EPI_QKV: SKD_LAUNCH((k_gemm_ws<R, EPI_QKV>), grid, blk, lds, s, a); break;
+    case EPI_RELU: SKD_LAUNCH((k_gemm_ws<R, EPI_RELU>), grid, blk, lds, s, a); break;
+    default: SKD_LAUNCH((k_gemm_ws<R, EPI_LOGITS>), grid, blk, lds, s, a); break;
+  }
+  return 0;
+}
+int bf16_gemm_ws(hipStream_t s, const GemmArgs &a, int epi, int R) {
+  dim3 grid;
+  int groups = 0;
+  if (!gemm_ws_shape(a, epi, R, grid, groups)) return -1;
+  int rc;
+  if (R == 1) rc = launch_gemm_ws<1>(s, a, epi, grid);
+  else if (R == 2) rc = launch_gemm_ws<2>(s, a, epi, grid);
+  else if (R == 3) rc = launch_gemm_ws<3>(s, a, epi, grid);
+  else rc = launch_gemm_ws<4>(s, a, epi, grid);
+  return rc < 0 ? -1 : groups;
 }
 
 // ------------------------------------------------------------------ tiled GEMM for the batched prompt

@@ -63,6 +63,8 @@ struct LayerW {
 
 struct GemmPlan {
   int R = 1, split = 1, U = 1, waves = 8;
+  bool ws = false;  // 128 batch rows: the wave-specialised kernel (weight-streaming waves + activation-loading waves)
+  int ws_rot = 0;   // workgroups start their K range at different stages
 };
 
 }  // namespace
@@ -398,7 +400,16 @@ const int32_t *bt_layer(const skd_state *st, int l) {
   return st->bt_dev + (size_t)l * st->cfg.batch * st->geom.max_pages;
 }
 
-// The four projections of a layer (the same shapes in every layer) against what the skinny GEMM can launch.
+// a decode projection on the kernel its plan names; returns the row groups launched or -1
+int launch_gemm(hipStream_t s, GemmArgs &ga, int epi, const GemmPlan &p) {
+  ga.ws_rot = p.ws_rot;
+  return p.ws ? bf16_gemm_ws(s, ga, epi, p.R) : bf16_gemm(s, ga, epi, p.R, p.U, p.waves);
+}
+int check_gemm(const GemmArgs &ga, int epi, const GemmPlan &p) {
+  return p.ws ? bf16_gemm_ws_check(ga, epi, p.R) : bf16_gemm_check(ga, epi, p.R, p.U, p.waves);
+}
+
+// The projections of a layer (the same shapes in every layer) and the LM head against what the kernels can launch.
 bool decode_shapes_ok(const skd_state *st) {
   const skd_config &c = st->cfg;
   const int d = c.d_model, f = c.ffn;
@@ -406,10 +417,10 @@ bool decode_shapes_ok(const skd_state *st) {
   ga.B = c.batch; ga.B_pad = st->B_pad;
   auto ok = [&](int N, int K, const GemmPlan &p, int epi) {
     ga.N = N; ga.K = K; ga.G = p.R; ga.split = p.split;
-    return bf16_gemm_check(ga, epi, p.R, p.U, p.waves) > 0;
+    return check_gemm(ga, epi, p) > 0;
   };
   return ok(3 * d, d, st->p_qkv, EPI_QKV) && ok(d, d, st->p_out, EPI_PARTIAL) && ok(f, d, st->p_ffn1, EPI_RELU) &&
-         ok(d, f, st->p_ffn2, EPI_PARTIAL);
+         ok(d, f, st->p_ffn2, EPI_PARTIAL) && ok(c.vocab, d, st->p_head, EPI_LOGITS);
 }
 
 // One column (all B rows at position t) through the given ascending layer list.  Everything that can refuse
@@ -454,7 +465,7 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       // q, k, v projection; the attention kernel files k and v into this layer's page slot for column t
       ga.W = (const bf16_t *)w.wqkv; ga.G = st->p_qkv.R; ga.A = a; ga.bias = w.bqkv; ga.N = 3 * d; ga.K = d; ga.split = 1;
       ga.q_out = q; ga.kv_new = st->kv_new;
-      { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = bf16_gemm(s, ga, EPI_QKV, st->p_qkv.R, st->p_qkv.U, st->p_qkv.waves); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_QKV); grc = launch_gemm(s, ga, EPI_QKV, st->p_qkv); }
       if (grc < 0) return SKD_ERR_SHAPE;
       AttnArgs aa{};
       aa.q = q; aa.kv_new = st->kv_new; aa.pool = (bf16_t *)st->pool; aa.bt_layer = bt_layer(st, l); aa.start = st->start_dev; aa.order = st->ragged ? st->order_dev : nullptr;
@@ -462,14 +473,14 @@ int run_column(skd_state *st, int t, const int32_t *tokens_dev, const int32_t *l
       { ProfScope ps_(st, SKD_PROF_ATTENTION); bf16_attention(s, aa); }
       // output projection -> partials; bias + residual + LayerNorm 2 in the reducer
       ga.W = (const bf16_t *)w.wo; ga.G = st->p_out.R; ga.A = o; ga.N = d; ga.K = d; ga.split = st->p_out.split; ga.partial = st->partial;
-      { ProfScope ps_(st, SKD_PROF_GEMM_OUT); grc = bf16_gemm(s, ga, EPI_PARTIAL, st->p_out.R, st->p_out.U, st->p_out.waves); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_OUT); grc = launch_gemm(s, ga, EPI_PARTIAL, st->p_out); }
       if (grc < 0) return SKD_ERR_SHAPE;
       { ProfScope ps_(st, SKD_PROF_REDUCE_LN); bf16_reduce_ln(s, st->partial, st->p_out.split, st->B_pad, w.bo, st->x, w.ln2_g, w.ln2_b, a, B, d); }
       ga.W = (const bf16_t *)w.w1; ga.G = st->p_ffn1.R; ga.A = a; ga.bias = w.b1; ga.N = f; ga.K = d; ga.split = 1; ga.act_out = u;
-      { ProfScope ps_(st, SKD_PROF_GEMM_FFN1); grc = bf16_gemm(s, ga, EPI_RELU, st->p_ffn1.R, st->p_ffn1.U, st->p_ffn1.waves); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_FFN1); grc = launch_gemm(s, ga, EPI_RELU, st->p_ffn1); }
       if (grc < 0) return SKD_ERR_SHAPE;
       ga.W = (const bf16_t *)w.w2; ga.G = st->p_ffn2.R; ga.A = u; ga.N = d; ga.K = f; ga.split = st->p_ffn2.split;
-      { ProfScope ps_(st, SKD_PROF_GEMM_FFN2); grc = bf16_gemm(s, ga, EPI_PARTIAL, st->p_ffn2.R, st->p_ffn2.U, st->p_ffn2.waves); }
+      { ProfScope ps_(st, SKD_PROF_GEMM_FFN2); grc = launch_gemm(s, ga, EPI_PARTIAL, st->p_ffn2); }
       if (grc < 0) return SKD_ERR_SHAPE;
       // the reducer of the last sub-block already applies the next LayerNorm:
       // LayerNorm 1 of the next ACTIVE layer, or the final LayerNorm
@@ -540,6 +551,22 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
     ov("SKD_W_OUT", st->p_out.waves, 4, 8); ov("SKD_W_FFN2", st->p_ffn2.waves, 4, 8);
   }
 
+  if (st->bf16 && st->B_pad == 128 && env_int("SKD_GEMM_WS", 1) != 0) {
+    // 128 batch rows: every projection whose K range divides into stages of 4 k-steps per workgroup
+    GemmArgs ga{};
+    ga.B = B; ga.B_pad = st->B_pad;
+    auto pick = [&](int N, int K, GemmPlan &p, int epi) {
+      ga.N = N; ga.K = K; ga.G = p.R; ga.split = p.split;
+      p.ws = bf16_gemm_ws_check(ga, epi, p.R) > 0;
+      // rotated K start: pays while the XCD's L2 (4 MiB) holds the activation matrix beside the weight stream
+      // (measured at 128 x 4096: FFN1 35.5 -> 33.7 us; at 128 x 16384, 4 MiB, FFN2 36.3 -> 38.8 us)
+      p.ws_rot = (long)st->B_pad * K * 2 <= (2L << 20);
+      const int e = env_int("SKD_WS_ROT", -1);
+      if (e == 0 || e == 1) p.ws_rot = e;
+    };
+    pick(3 * d, d, st->p_qkv, EPI_QKV); pick(d, d, st->p_out, EPI_PARTIAL); pick(f, d, st->p_ffn1, EPI_RELU);
+    pick(d, f, st->p_ffn2, EPI_PARTIAL); pick(V, d, st->p_head, EPI_LOGITS);
+  }
   if (st->bf16 && !decode_shapes_ok(st)) return fail(SKD_ERR_SHAPE);  // an override the kernels cannot launch
   {  // the device this state lives on, and that device's copy of the static scratch array
     hipError_t e = hipGetDevice(&st->device);
@@ -833,7 +860,7 @@ static int head_logits(skd_state *st, float *logits_target, bool want_argmax = t
     ga.B = B; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.G = st->p_head.R; ga.A = (const bf16_t *)st->a;  // a = final LayerNorm output
     ga.N = V; ga.K = d; ga.split = 1; ga.logits = logits_target; ga.pmax = st->pmax; ga.pidx = st->pidx;
     int groups = 0;
-    { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves); }
+    { ProfScope ps_(st, SKD_PROF_LM_HEAD); groups = launch_gemm(s, ga, EPI_LOGITS, st->p_head); }
     if (groups < 0) return SKD_ERR_SHAPE;
     if (want_argmax) { ProfScope ps_(st, SKD_PROF_ARGMAX); bf16_argmax_final(s, st->pmax, st->pidx, groups, st->B_pad, st->argmax_dev, B); }
   }
@@ -881,9 +908,9 @@ extern "C" int skd_logits_argmax_noalloc(skd_state *st, int32_t *tokens_out, flo
   GemmArgs ga{};
   ga.B = c.batch; ga.B_pad = st->B_pad; ga.W = (const bf16_t *)st->head; ga.G = st->p_head.R; ga.A = (const bf16_t *)st->a;
   ga.N = c.vocab; ga.K = c.d_model; ga.split = 1; ga.logits = logits_out; ga.pmax = pmax; ga.pidx = pidx;
-  if (bf16_gemm_check(ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves) != groups) return SKD_ERR_SHAPE;
+  if (check_gemm(ga, EPI_LOGITS, st->p_head) != groups) return SKD_ERR_SHAPE;
   // every partial the final reduction reads is written by the projection of this same call: nothing to clear
-  (void)bf16_gemm(s, ga, EPI_LOGITS, st->p_head.R, st->p_head.U, st->p_head.waves);
+  (void)launch_gemm(s, ga, EPI_LOGITS, st->p_head);
   bf16_argmax_final(s, pmax, pidx, groups, st->B_pad, st->argmax_dev, c.batch);
   HIPCHECK(hipGetLastError());
   st->have_argmax = true;

@@ -98,6 +98,7 @@ struct GemmArgs {
   const float *bias;   // [N] or null
   int N, K, B, B_pad;
   int split;           // workgroups along K (grid.y)
+  int ws_rot;          // bf16_gemm_ws: workgroups start their K range at different stages
   // batched prompt processing: activation rows are the real (sequence, position) pairs of `rm`, handled in
   // 256 x 256 tiles or in chunks of B_pad rows along grid.z.  rows = 0: one chunk whose rows are the batch (decode).
   int rows;            // rows of the prompt pass, padded to 256
@@ -123,6 +124,11 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epilogue, int R, int U, int 
 // The same shape checks without a launch (only N, K, B_pad, G, split and rows of `a` are read): groups or -1.
 int bf16_gemm_check(const GemmArgs &a, int epilogue, int R, int U, int waves);
 int bf16_gemm_groups(int N, int R);
+// Decode projections with B_pad = 128 on the wave-specialised kernel (weight-streaming waves + activation-loading
+// waves); (K / 32 / split) must be a multiple of 4.  Returns the row groups launched, or -1 (nothing launched) for
+// shapes it does not handle; bf16_gemm_ws_check answers the same without launching.
+int bf16_gemm_ws(hipStream_t s, const GemmArgs &a, int epilogue, int R);
+int bf16_gemm_ws_check(const GemmArgs &a, int epilogue, int R);
 // Batched prompt only (a.rows > 0; EPI_QKV_ROWS, EPI_RESID or EPI_RELU): 256 x 256 output tiles with LDS-staged
 // operands.  Needs rows % 256 == 0 and N % 256 == 0 (K % 32 == 0 as everywhere); returns -1 otherwise (nothing launched).
 int bf16_gemm_tile(hipStream_t s, const GemmArgs &a, int epilogue);

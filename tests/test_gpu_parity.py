@@ -75,6 +75,29 @@ def test_batch_tiles_bf16(B):
     compare(MID64, w, pr, P, N, 2, 5, BF16_TOL, dtype=skd.BF16)
 
 
+@pytest.mark.parametrize("ws", ["1", "0"])
+@pytest.mark.parametrize("B", [113, 128])
+def test_batch_128_projection_kernels(B, ws):
+    # 8 activation tiles (batch padded to 128): the projections run on the kernel with separate weight-streaming
+    # and activation-loading waves (K ranges of 4, 12 and 16 stages per workgroup here: a ring that never fills,
+    # and one that wraps), or, switched off, on the general skinny kernel; ragged left padding
+    import os
+    shape = S.ModelShape(L=3, d=512, H=4, f=1536, V=1000, max_pos=64)
+    w = bf16_weights(shape, 91)
+    P, N = 11, 24
+    pr = S.make_prompts(B, P, shape.V, 92)
+    mask = S.make_ragged_mask(B, P, 2, P, seed=93)
+    old = os.environ.get("SKD_GEMM_WS")
+    os.environ["SKD_GEMM_WS"] = ws
+    try:
+        compare(shape, w, pr, P, N, 1, 3, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, min_decided=0.0)
+    finally:
+        if old is None:
+            os.environ.pop("SKD_GEMM_WS", None)
+        else:
+            os.environ["SKD_GEMM_WS"] = old
+
+
 @pytest.mark.parametrize("dtype,tol", [(skd.FP32, FP32_TOL), (skd.BF16, BF16_TOL)])
 def test_warmup_layer(dtype, tol):
     # one warm-up layer at the bottom + top window (the setting of every Table 2 row)
