@@ -359,6 +359,8 @@ def main():
     ap.add_argument("--reps", type=int, default=5, help="repetitions of the timed region (the line reports the median)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="only the named workload (default: the other contract workloads are measured as well)")
+    ap.add_argument("--no-table2-presets", action="store_true",
+                    help="skip the paper's Table 2 presets (default: measured at the contract batch and lengths)")
     ap.add_argument("--contiguous", action="store_true",
                     help="time the FIRST --steps steps in one bracket, with no pass over the whole generation "
                          "(bounded number of launches: for hardware-counter runs)")
@@ -427,30 +429,67 @@ def main():
         "config": m.pop("config"), "device_copy_read_plus_write_gbs": copy_gbs,
     }
     res.update(m)
-    # the other contract workloads (same measurement, fewer repetitions, no per-class table): driver-visible figures
-    others = {}
-    if not args.no_other_workloads and args.workload == DEFAULT_WORKLOAD:
-        order = sorted(OTHER_WORKLOADS, key=lambda n: WORKLOADS[n][0] != shape)   # same-shape workloads first
-        for name in order:
-            o = measure_workload(skd, torch, name, weights_of(WORKLOADS[name][0]), args.steps, args.warmup,
-                                 max(3, args.reps // 2 + 1), not args.no_profile, args)
-            keep = ("value", "unit", "steps", "ms_per_step", "hbm_gbs", "hbm_frac_of_8TBs", "algorithmic_gb_per_step",
-                    "prefill_s", "speedup_vs_full_depth", "ideal_layer_ratio", "ideal_byte_ratio",
-                    "ms_per_step_repeats", "equal_depth_step_ms")
-            others[name] = {k: o[k] for k in keep if k in o}
-            others[name]["config"] = o["config"]
-            if "full_depth" in o:
-                others[name]["full_depth"] = {k: o["full_depth"][k] for k in ("value", "ms_per_step")}
-            if o.get("roofline"):
-                others[name]["roofline"] = {k: o["roofline"][k] for k in ("kernel", "achieved", "frac", "traffic",
-                                                                          "bytes_per_launch", "avg_launch_us")}
-            if "kernels" in o:
-                others[name]["kernels_gbs"] = {k: (round(v["gbs"], 1) if v["gbs"] else None)
-                                               for k, v in o["kernels"].items()}
+    # The other contract workloads (same measurement, fewer repetitions), and Table 2's eight presets (warm-up layer,
+    # min and max layer per target speed-up) at the batch and lengths of the contract workload with the same model
+    # shape, whose full-depth leg is theirs as well (same shapes, n = L everywhere).  One model's weights are resident
+    # at a time: everything of the default workload's shape first.
+    others, presets = {}, {}
+    want_others = not args.no_other_workloads and args.workload == DEFAULT_WORKLOAD
+    want_presets = want_others and not args.no_table2_presets and not args.no_full_depth
+
+    class _SkipLegOnly:
+        pass
+    pa = _SkipLegOnly()
+    pa.__dict__.update(vars(args))
+    pa.no_full_depth = True
+
+    def other(name):
+        o = measure_workload(skd, torch, name, weights_of(WORKLOADS[name][0]), args.steps, args.warmup,
+                             max(3, args.reps // 2 + 1), not args.no_profile, args)
+        keep = ("value", "unit", "steps", "ms_per_step", "hbm_gbs", "hbm_frac_of_8TBs", "algorithmic_gb_per_step",
+                "prefill_s", "speedup_vs_full_depth", "ideal_layer_ratio", "ideal_byte_ratio",
+                "ms_per_step_repeats", "equal_depth_step_ms")
+        others[name] = {k: o[k] for k in keep if k in o}
+        others[name]["config"] = o["config"]
+        if "full_depth" in o:
+            others[name]["full_depth"] = {k: o["full_depth"][k] for k in ("value", "ms_per_step")}
+        if o.get("roofline"):
+            others[name]["roofline"] = {k: o["roofline"][k] for k in ("kernel", "achieved", "frac", "traffic",
+                                                                      "bytes_per_launch", "avg_launch_us")}
+        if "kernels" in o:
+            others[name]["kernels_gbs"] = {k: (round(v["gbs"], 1) if v["gbs"] else None)
+                                           for k, v in o["kernels"].items()}
+            others[name]["kernels_avg_us"] = {k: round(v["avg_us"], 2) for k, v in o["kernels"].items()}
+
+    def preset(name, full_depth_tok_s):
+        sh, _B, _P, _T, lo, hi, _r, wl_ = WORKLOADS[name]
+        o = measure_workload(skd, torch, name, weights_of(sh), args.steps, args.warmup, 3, False, pa)
+        presets[name] = {"target_speedup": int(name.rsplit("-", 1)[1][0]), "warmup_min_max_layers": [wl_, lo, hi],
+                         "value": o["value"], "unit": "tokens/s", "ms_per_step": o["ms_per_step"],
+                         "hbm_frac_of_8TBs": o["hbm_frac_of_8TBs"], "mean_n": o["config"]["mean_n"],
+                         "speedup_vs_full_depth": o["value"] / full_depth_tok_s,
+                         "ideal_layer_ratio": sh.L / o["config"]["mean_n"]}
+
+    if want_others:
+        for name in OTHER_WORKLOADS:
+            if WORKLOADS[name][0] == shape:
+                other(name)
+        if want_presets and "full_depth" in res:
+            for name in sorted(n for n in WORKLOADS if n.startswith("opt6.7b_b32_p512_t256_table2-")):
+                preset(name, res["full_depth"]["value"])
+        for name in OTHER_WORKLOADS:
+            if WORKLOADS[name][0] != shape:
+                other(name)
+        base13 = others.get("opt1.3b_b16_p256_t256_24to12", {}).get("full_depth", {}).get("value")
+        if want_presets and base13:
+            for name in sorted(n for n in WORKLOADS if n.startswith("opt1.3b_b16_p256_t256_table2-")):
+                preset(name, base13)
     weights.clear()
     torch.cuda.empty_cache()
     if others:
         res["other_workloads"] = others
+    if presets:
+        res["table2_presets"] = presets
     res["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(shape, B, P, T, n_min, n_max)
     print(json.dumps(res))
 
