@@ -933,7 +933,7 @@ void bf16_reduce_ln(hipStream_t s, const float *partial, int split, int B_pad, c
 }
 
 // ------------------------------------------------------------------ decode attention over the paged KV cache
-// One workgroup of NW waves (2, 4, 8 or 16) per (row, head, split).  Wave w takes
+// One workgroup of NW waves (1, 2, 4, 8 or 16) per (row, head, split).  Wave w takes
 // 32-key blocks first + w, first + w + NW, ...; each block is 2 K tiles (QK^T:
 // 2 * DH/32 MFMAs, q replicated over the 16 MFMA columns) and one V block
 // (DH/16 MFMAs).  Online softmax per wave in fp32; the waves (and, with
@@ -977,18 +977,26 @@ __global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 wa
   // with several splits possibly by another workgroup while this one stores: the result does not depend on
   // what that load sees, because keys >= len get weight 0 and every slot of the pool holds finite bits at all
   // times (the pool is zeroed when it is created and only finite k and v are ever filed), so 0 x slot = 0.
+  // (a one-wave workgroup has 64 threads for 128 elements: EPT elements per thread, e = threadIdx.x + i * NW * 64)
+  constexpr int EPT = (DH + NW * 64 - 1) / (NW * 64);
   const bool with_new = blockIdx.y == gridDim.y - 1 && len >= 0;
-  float q_e = 0.f, k_e = 0.f, v_e = 0.f;
-  bf16_t k_bits = 0, v_bits = 0;
+  float q_e[EPT], k_e[EPT], v_e[EPT];
+  bf16_t k_bits[EPT], v_bits[EPT];
   int page_t = 0;
-  if (with_new && threadIdx.x < DH) {
-    const bf16_t *kr = a.kv_new + ((long)b * 2) * d + h * DH;
-    k_bits = kr[threadIdx.x];
-    v_bits = kr[d + threadIdx.x];
-    q_e = bf2f(a.q[(long)b * d + h * DH + threadIdx.x]);
-    k_e = bf2f(k_bits);
-    v_e = bf2f(v_bits);
-    page_t = bt_row[len / a.kv.page_tokens];
+#pragma unroll
+  for (int i = 0; i < EPT; ++i) {
+    q_e[i] = k_e[i] = v_e[i] = 0.f;
+    k_bits[i] = v_bits[i] = 0;
+    const int e = (int)threadIdx.x + i * NW * 64;
+    if (with_new && e < DH) {
+      const bf16_t *kr = a.kv_new + ((long)b * 2) * d + h * DH;
+      k_bits[i] = kr[e];
+      v_bits[i] = kr[d + e];
+      q_e[i] = bf2f(a.q[(long)b * d + h * DH + e]);
+      k_e[i] = bf2f(k_bits[i]);
+      v_e[i] = bf2f(v_bits[i]);
+      page_t = bt_row[len / a.kv.page_tokens];
+    }
   }
 
   floatx4 O[VM];
@@ -1086,19 +1094,24 @@ __global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 wa
 #pragma unroll
       for (int i = 0; i < 4; ++i) sm_o[wave][16 * m + 4 * grp + i] = O[m][i];
   }
-  {  // q . k_t: waves 0 .. DH/64-1 hold the products
-    float dot = q_e * k_e;
+  {  // q . k_t: the first waves (the threads below DH) hold the products
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) dot += q_e[i] * k_e[i];
     for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
     if (lane == 0) sm_dot[wave] = dot;
   }
   __syncthreads();
-  if (threadIdx.x < DH) {
-    const int e = threadIdx.x;
+  constexpr int NDW = NW < DH / 64 ? NW : DH / 64;  // waves whose sm_dot holds products
+#pragma unroll
+  for (int i = 0; i < EPT; ++i) {
+    const int e = (int)threadIdx.x + i * NW * 64;
+    if (e >= DH) continue;
     float M = sm_m[0];
     for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w]);
     float s_t = 0.f;
     if (with_new) {
-      for (int w = 0; w < DH / 64; ++w) s_t += sm_dot[w];
+      for (int w = 0; w < NDW; ++w) s_t += sm_dot[w];
       s_t *= scale;
       M = fmaxf(M, s_t);
     }
@@ -1110,7 +1123,7 @@ __global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 wa
     }
     if (with_new) {
       const float f = __expf(s_t - M);
-      num += f * v_e;
+      num += f * v_e[i];
       den += f;
     }
     if (a.splits == 1) {
@@ -1124,8 +1137,8 @@ __global__ __launch_bounds__(NW * 64, 4) void k_attention(AttnArgs a) {  // 4 wa
     if (with_new) {
       bf16_t *pg = a.pool + (long)page_t * a.kv.page_elems;
       const int tt = len % a.kv.page_tokens;
-      pg[kv_k_off(h, tt, e, a.kv)] = k_bits;
-      pg[kv_v_off(h, tt, e, a.kv)] = v_bits;
+      pg[kv_k_off(h, tt, e, a.kv)] = k_bits[i];
+      pg[kv_v_off(h, tt, e, a.kv)] = v_bits[i];
     }
   }
 }
@@ -1147,15 +1160,17 @@ __global__ void k_attn_merge(AttnArgs a) {
 
 void bf16_attention(hipStream_t s, const AttnArgs &a) {
   const dim3 grid(a.B * a.kv.H, a.splits);
-  const int nw = a.waves >= 16 ? 16 : a.waves >= 8 ? 8 : a.waves >= 4 ? 4 : 2;
+  const int nw = a.waves >= 16 ? 16 : a.waves >= 8 ? 8 : a.waves >= 4 ? 4 : a.waves >= 2 ? 2 : 1;
   if (a.kv.dh == 64) {
-    if (nw == 16) SKD_LAUNCH((k_attention<64, 16>), grid, dim3(1024), 0, s, a);
+    if (nw == 1) SKD_LAUNCH((k_attention<64, 1>), grid, dim3(64), 0, s, a);
+    else if (nw == 16) SKD_LAUNCH((k_attention<64, 16>), grid, dim3(1024), 0, s, a);
     else if (nw == 8) SKD_LAUNCH((k_attention<64, 8>), grid, dim3(512), 0, s, a);
     else if (nw == 2) SKD_LAUNCH((k_attention<64, 2>), grid, dim3(128), 0, s, a);
     else SKD_LAUNCH((k_attention<64, 4>), grid, dim3(256), 0, s, a);
     if (a.splits > 1) SKD_LAUNCH(k_attn_merge<64>, dim3(a.B * a.kv.H), dim3(64), 0, s, a);
   } else {
-    if (nw == 16) SKD_LAUNCH((k_attention<128, 16>), grid, dim3(1024), 0, s, a);
+    if (nw == 1) SKD_LAUNCH((k_attention<128, 1>), grid, dim3(64), 0, s, a);
+    else if (nw == 16) SKD_LAUNCH((k_attention<128, 16>), grid, dim3(1024), 0, s, a);
     else if (nw == 8) SKD_LAUNCH((k_attention<128, 8>), grid, dim3(512), 0, s, a);
     else if (nw == 2) SKD_LAUNCH((k_attention<128, 2>), grid, dim3(128), 0, s, a);
     else SKD_LAUNCH((k_attention<128, 4>), grid, dim3(256), 0, s, a);

@@ -430,6 +430,7 @@ def test_prompt_tiles_in_xcd_order_page_contents():
     {"SKD_ATTN_SPLITS": "1"}, {"SKD_ATTN_SPLITS": "4"}, {"SKD_PREFILL_BATCHED": "0", "SKD_ATTN_SPLITS": "8"},
     {"SKD_ATTN_WAVES": "4", "SKD_ATTN_SPLITS": "2"}, {"SKD_ATTN_WAVES": "8", "SKD_ATTN_SPLITS": "1"},
     {"SKD_ATTN_WAVES": "16", "SKD_ATTN_SPLITS": "3"}, {"SKD_ATTN_WAVES": "2"},
+    {"SKD_ATTN_WAVES": "1"}, {"SKD_ATTN_WAVES": "1", "SKD_ATTN_SPLITS": "2"},
 ])
 def test_launch_shape_overrides(env):
     # every launch shape the planner can choose (tile rows per workgroup, k-steps per buffer, waves, split-K,
@@ -491,6 +492,20 @@ def test_argmax_exact_ties_take_lowest_index(dtype, far):
             dec.decode_step(P + k, tape[k])
             _, otok = odec.column(P + k, tape[k], O.active_layers(P + k, P, N, 2, 4, 0, shape.L))
     odec.close()
+
+
+def test_one_wave_attention_head_dim_64():
+    # one wave per (row, head) is what batches of 128 rows x 32 heads get; forced here on 64-wide heads (one element
+    # of the head per thread; 128-wide heads, two per thread, are covered by the launch-shape walk above)
+    import os
+    w = bf16_weights(MID64, 95)
+    pr = S.make_prompts(7, 45, MID64.V, 96)
+    mask = S.make_ragged_mask(7, 45, 3, 45, seed=97)
+    os.environ["SKD_ATTN_WAVES"] = "1"
+    try:
+        compare(MID64, w, pr, 45, 110, 2, 5, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, min_decided=0.0)
+    finally:
+        os.environ.pop("SKD_ATTN_WAVES", None)
 
 
 def test_vocabulary_above_sampler_limit():
