@@ -144,12 +144,16 @@ __global__ void k_f32_argmax(const float *logits, int32_t *tokens, int V) {
 //   token = first index of the nucleus whose running mass (ascending index) exceeds u * mass(nucleus).
 // Every sum is taken in a fixed order, so a given (logits, u) always yields the same token.
 constexpr int SAMPLE_C = 64;
+constexpr int SAMPLE_CAND = 1024;  // candidates one wave finishes alone (16 per lane; 32 per lane spills registers)
 
 // RC: rows compiled in (>= R); 52 rows cover vocabularies up to 53248 without register spills
 template <int RC>
 __global__ __launch_bounds__(1024) void k_sample_top_p(const float *logits, int V, float inv_temp, float top_p,
                                                        const float *u, int32_t *tokens) {
   __shared__ float sh[16], wmass[16];
+  __shared__ int wcount[16];
+  __shared__ float cand_p[SAMPLE_CAND];  // candidates of the short cut, ascending token index
+  __shared__ int cand_i[SAMPLE_CAND];
   __shared__ float rows[RC * 64];  // the rows of the one wave that walks its range
   __shared__ int last_in, hit_tok;
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -174,9 +178,111 @@ __global__ __launch_bounds__(1024) void k_sample_top_p(const float *logits, int 
     p[i] = p[i] > -1.0e38f ? expf(p[i] - mx) : 0.f;
     loc += p[i];
   }
-  const float target = top_p * block_sum(loc, sh);
+  const float total = block_sum(loc, sh);
+  const float target = top_p * total;
+
+  // The threshold is found bit by bit on the float bit pattern, from the top.  The first 8 rounds (sign excluded:
+  // the exponent bits) are taken by the whole workgroup; they fix the threshold to within a factor of two, and every
+  // token below that lower bound is out of the nucleus whatever the remaining bits turn out to be.  If the tokens at
+  // or above it are few (<= SAMPLE_CAND: nearly always at the paper's temperature 0.3, where the nucleus is a few
+  // hundred tokens), they are compacted in index order into LDS and one wave finishes the row alone with wave-level
+  // sums: no workgroup barrier in the remaining 23 rounds.  For every trial threshold at or above the lower bound
+  // the sums run over the same tokens as in the whole-workgroup search, so the threshold is the same up to the
+  // order of the fp32 additions.
   unsigned T = 0;
-  for (int bit = 30; bit >= 0; --bit) {
+  for (int bit = 30; bit >= 23; --bit) {
+    const unsigned cand = T | (1u << bit);
+    float m = 0;
+#pragma unroll
+    for (int i = 0; i < RC; ++i) m += (__float_as_uint(p[i]) >= cand) ? p[i] : 0.f;  // absent tokens hold zeros
+    if (block_sum(m, sh) >= target) T = cand;  // uniform decision: every thread sees the same sum
+  }
+  {
+    const unsigned lower = max(T, 1u);  // bit pattern 0 = an absent token or an underflowed probability: never a candidate
+    int cnt = 0;  // per lane first (a ballot per row here would be kept for the compaction below: 2 SGPRs per row)
+    const unsigned below = lower - 1u;  // lower >= 1
+#pragma unroll
+    for (int i = 0; i < RC; ++i) cnt += (__float_as_uint(p[i]) > below) ? 1 : 0;  // non-negative floats order like their bits
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    __syncthreads();  // sh (read by block_sum above) is free
+    if (lane == 0) wcount[wave] = cnt;
+    __syncthreads();
+    int C = 0, wbase = 0;
+    for (int w = 0; w < 16; ++w) {
+      if (w < wave) wbase += wcount[w];
+      C += wcount[w];
+    }
+    // uniform over the workgroup, and said so: as a divergent branch it would keep the 52-64 probabilities of the
+    // other path alive in registers next to this path's candidates
+    C = __builtin_amdgcn_readfirstlane(C);
+    wbase = __builtin_amdgcn_readfirstlane(wbase);
+    if (C <= SAMPLE_CAND) {
+      int pos = wbase;
+#pragma unroll
+      for (int i = 0; i < RC; ++i) {
+        // (the counting loop tests "> lower - 1", this one ">= lower": the same test, but the compiler recomputes it
+        // here instead of keeping one lane mask per row from there)
+        const bool c = __float_as_uint(p[i]) >= lower;
+        const unsigned long long m = __ballot(c);
+        if (c) {
+          const int k = pos + __popcll(m & ((1ull << lane) - 1ull));
+          cand_p[k] = p[i];
+          cand_i[k] = base + 64 * i;
+        }
+        pos += __popcll(m);
+        __builtin_amdgcn_sched_barrier(0);  // row by row: hoisted, the rows' lane masks would need 2 SGPRs each
+      }
+      __syncthreads();
+      if (__builtin_amdgcn_readfirstlane(wave) == 0) {
+        constexpr int PER = SAMPLE_CAND / 64;  // lane l owns candidates l * PER .. l * PER + PER - 1 (index order)
+        float v[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) v[j] = lane * PER + j < C ? cand_p[lane * PER + j] : 0.f;
+        for (int bit = 22; bit >= 0; --bit) {
+          const unsigned cand = T | (1u << bit);
+          float m = 0;
+#pragma unroll
+          for (int j = 0; j < PER; ++j) m += (__float_as_uint(v[j]) >= cand) ? v[j] : 0.f;
+          if (wave_sum(m) >= target) T = cand;
+        }
+        float lm = 0;
+        int last = -1;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+          if (__float_as_uint(v[j]) < T) v[j] = 0.f;
+          lm += v[j];
+          if (v[j] > 0.f) last = lane * PER + j;
+        }
+        float inc = lm;  // inclusive prefix of the lanes' masses = prefix in index order
+        for (int off = 1; off < 64; off <<= 1) {
+          const float t = __shfl_up(inc, off);
+          if (lane >= off) inc += t;
+        }
+        const float goal = u[b] * __shfl(inc, 63);
+        const unsigned long long over = __ballot(inc > goal);
+        int k = -1;
+        if (over) {
+          const int L = (int)__builtin_ctzll(over);
+          if (lane == L) {
+            float run = inc - lm;
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+              run += v[j];
+              if (k < 0 && v[j] > 0.f && run > goal) k = lane * PER + j;
+            }
+            if (k < 0) k = last;  // rounding between the lane's two summation orders: its last member
+          }
+          k = __shfl(k, L);
+        } else {  // rounding at the very end: the last member of the nucleus
+          for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o));
+          k = last;
+        }
+        if (lane == 0) tokens[b] = k >= 0 ? cand_i[k] : 0;
+      }
+      return;
+    }
+  }
+  for (int bit = 22; bit >= 0; --bit) {
     const unsigned cand = T | (1u << bit);
     float m = 0;
 #pragma unroll

@@ -317,6 +317,57 @@ def test_sampling_head_full_vocab_distribution():
         assert abs((toks == i).mean() - p[i] / mass) < 2.5 / len(toks) + 1e-3
 
 
+def test_sampling_head_full_vocab_both_paths():
+    # vocabulary 50272, rows with different logits.  After the exponent rounds of the threshold search the tokens
+    # that can still be in the nucleus are few at low temperature (one wave then finishes the row alone on the
+    # compacted candidates) and thousands at high temperature or top-p 1 (the whole workgroup searches on).  Both
+    # paths against the oracle's sampler on the same logits and uniform numbers.
+    shape = S.ModelShape(L=1, d=128, H=2, f=128, V=50272, max_pos=8)
+    w = S.make_weights(shape, 5)
+    g = np.random.Generator(np.random.Philox(key=[5, 99]))
+    w["lm_head"] = (g.standard_normal(size=(shape.V, shape.d), dtype=np.float32) * np.float32(0.09))
+    w = S.weights_to_bf16_values(w)
+    B, P, N = 8, 2, 4
+    pr = S.make_prompts(B, P, shape.V, 6)
+    cfg = skd.make_config(shape, B, P, N, 1, 1, dtype=skd.BF16)
+    rng = np.random.default_rng(7)
+
+    def candidates(z, temperature, top_p):
+        # tokens at or above the largest power of two whose upper set reaches the target mass
+        pz = np.exp((z - z.max()) / temperature)
+        for e in range(0, -127, -1):
+            if pz[pz >= 2.0 ** e].sum() >= top_p * pz.sum():
+                return int((pz >= 2.0 ** e).sum())
+        return z.size
+
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        _, lg = dec.logits_argmax()
+        for temperature, top_p, few in ((0.3, 0.7, True), (0.2, 0.9, True), (0.5, 0.7, False), (3.0, 0.7, False),
+                                        (1.0, 1.0, False)):
+            cand = np.array([candidates(lg[b].astype(np.float64), temperature, top_p) for b in range(B)])
+            assert (cand <= 600).all() if few else (cand >= 2000).all(), (temperature, top_p, cand)   # limit: 1024
+            checked = 0
+            for _ in range(6):
+                u = rng.random(B).astype(np.float32)
+                tok, _ = dec.logits_sample(u, temperature, top_p, want_logits=False)
+                for b in range(B):
+                    ref, m_set, m_run = O.op_sample(lg[b], temperature, top_p, float(u[b]))
+                    if m_set > 1e-5 and m_run > 1e-5:
+                        assert tok[b] == ref, (temperature, top_p, b, u[b], m_set, m_run)
+                        checked += 1
+            if temperature <= 0.5:
+                assert checked >= 24, (temperature, top_p, checked)
+            else:
+                # nearly flat over tens of thousands of tokens: the oracle's decision margins are below fp32 rounding
+                # almost everywhere, so check membership instead: every sample lies in the nucleus
+                for b in range(B):
+                    pz = np.exp((lg[b].astype(np.float64) - lg[b].max()) / temperature)
+                    srt = np.sort(pz)[::-1]
+                    k = int(np.searchsorted(np.cumsum(srt), top_p * pz.sum(), side="left"))
+                    assert pz[tok[b]] >= srt[min(k, srt.size - 1)] * (1 - 1e-4), (temperature, top_p, b)
+
+
 @pytest.mark.parametrize("dtype,tol", [(skd.FP32, FP32_TOL), (skd.BF16, BF16_TOL)])
 def test_minimal_sizes(dtype, tol):
     # one row, one prompt token, two decode steps; and a prompt that ends exactly on a page boundary
