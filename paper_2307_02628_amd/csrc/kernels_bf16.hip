@@ -453,7 +453,8 @@ int bf16_gemm(hipStream_t s, const GemmArgs &a, int epi, int R, int U, int waves
 //   that wave w multiplies.  One bare s_barrier per stage orders the ring (as in the tiled prompt GEMM below).
 // With a.ws_rot the workgroups start their K range at different stages (and wrap), so that at any moment the
 // CUs of an XCD ask its L2 for different lines; the sum over k is then taken in that rotated order: fixed for a
-// given launch shape, hence run-to-run deterministic, but not the same order in every workgroup.
+// given launch shape, hence run-to-run deterministic, but not the same order in every workgroup (the caller leaves
+// it off for the LM head, where identical vocabulary rows are to give identical logits).
 constexpr int WS_NS = 4;  // ring stages
 constexpr int WS_CW = 4;  // MFMA waves = loader waves = k-steps per stage
 constexpr int WS_MB = 8;  // batch tiles

@@ -560,9 +560,11 @@ static int create_impl(const skd_config *cfg, const skd_weights *w, void *hip_st
       p.ws = bf16_gemm_ws_check(ga, epi, p.R) > 0;
       // rotated K start: pays while the XCD's L2 (4 MiB) holds the activation matrix beside the weight stream
       // (measured at 128 x 4096: FFN1 35.5 -> 33.7 us; at 128 x 16384, 4 MiB, FFN2 36.3 -> 38.8 us)
-      p.ws_rot = (long)st->B_pad * K * 2 <= (2L << 20);
+      // Not for the LM head: there every vocabulary row keeps the same summation order, so that identical rows give
+      // identical logits at every batch size (ties are then broken by index, as documented), and it gains nothing.
+      p.ws_rot = epi != EPI_LOGITS && (long)st->B_pad * K * 2 <= (2L << 20);
       const int e = env_int("SKD_WS_ROT", -1);
-      if (e == 0 || e == 1) p.ws_rot = e;
+      if (e == 0 || (e == 1 && epi != EPI_LOGITS)) p.ws_rot = e;
     };
     pick(3 * d, d, st->p_qkv, EPI_QKV); pick(d, d, st->p_out, EPI_PARTIAL); pick(f, d, st->p_ffn1, EPI_RELU);
     pick(d, f, st->p_ffn2, EPI_PARTIAL); pick(V, d, st->p_head, EPI_LOGITS);

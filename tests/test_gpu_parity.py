@@ -77,12 +77,15 @@ def test_batch_tiles_bf16(B):
 
 @pytest.mark.parametrize("ws", ["1", "0"])
 @pytest.mark.parametrize("B", [113, 128])
-def test_batch_128_projection_kernels(B, ws):
+@pytest.mark.parametrize("small", [False, True])
+def test_batch_128_projection_kernels(B, ws, small):
     # 8 activation tiles (batch padded to 128): the projections run on the kernel with separate weight-streaming
     # and activation-loading waves (K ranges of 4, 12 and 16 stages per workgroup here: a ring that never fills,
     # and one that wraps), or, switched off, on the general skinny kernel; ragged left padding
     import os
     shape = S.ModelShape(L=3, d=512, H=4, f=1536, V=1000, max_pos=64)
+    if small:   # K ranges of one and two stages: a ring that is never ahead, weight prefetches past the end
+        shape = S.ModelShape(L=2, d=128, H=2, f=256, V=300, max_pos=64)
     w = bf16_weights(shape, 91)
     P, N = 11, 24
     pr = S.make_prompts(B, P, shape.V, 92)
@@ -90,7 +93,7 @@ def test_batch_128_projection_kernels(B, ws):
     old = os.environ.get("SKD_GEMM_WS")
     os.environ["SKD_GEMM_WS"] = ws
     try:
-        compare(shape, w, pr, P, N, 1, 3, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, min_decided=0.0)
+        compare(shape, w, pr, P, N, 1, shape.L, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, min_decided=0.0)
     finally:
         if old is None:
             os.environ.pop("SKD_GEMM_WS", None)
@@ -504,12 +507,13 @@ def test_launch_shape_overrides(env):
                 os.environ[k] = v
 
 
-@pytest.mark.parametrize("dtype", [skd.FP32, skd.BF16])
+@pytest.mark.parametrize("dtype,B", [(skd.FP32, 5), (skd.BF16, 5), (skd.BF16, 128)])
 @pytest.mark.parametrize("far", [False, True])
-def test_argmax_exact_ties_take_lowest_index(dtype, far):
+def test_argmax_exact_ties_take_lowest_index(dtype, far, B):
     # greedy head: the LOWEST index attaining the maximum.  An untied LM head with duplicated rows makes every
     # logit tie exactly with its twin: 500 rows away (another workgroup of the LM-head projection, merged by the
-    # final reduction) or in the next row (same 16-row tile, merged inside the projection's epilogue).
+    # final reduction) or in the next row (same 16-row tile, merged inside the projection's epilogue).  Batch 128 runs
+    # the LM head on the wave-specialised kernel, which keeps one summation order for all vocabulary rows.
     shape = S.TINY
     w = S.make_weights(shape, 0)
     lm = np.array(w["tok_emb"], copy=True)
@@ -520,7 +524,7 @@ def test_argmax_exact_ties_take_lowest_index(dtype, far):
     w["lm_head"] = lm
     if dtype == skd.BF16:
         w = S.weights_to_bf16_values(w)
-    B, P, N = 5, 6, 12
+    P, N = 6, 12
     pr = S.make_prompts(B, P, shape.V, 44)
     tape = S.make_token_tape(B, N - P, shape.V, 45)
     cfg = skd.make_config(shape, B, P, N, 2, 4, dtype=dtype)
