@@ -563,6 +563,23 @@ def test_one_wave_attention_head_dim_64():
         os.environ.pop("SKD_ATTN_WAVES", None)
 
 
+def test_unlaunchable_override_is_refused_at_create():
+    # a launch-shape override the kernels cannot run (K = 1536 = 48 k-steps does not split 7 ways) is caught when the
+    # state is created, not in the middle of a column: skd_create returns SKD_ERR_SHAPE and no state exists
+    import os
+    w = bf16_weights(MID, 2)
+    cfg = skd.make_config(MID, 2, 4, 8, 1, 3, dtype=skd.BF16)
+    os.environ["SKD_S_FFN2"] = "7"
+    try:
+        with pytest.raises(skd.SkdError) as e:
+            skd.Decoder(cfg, w)
+        assert e.value.code == skd.ERR_SHAPE
+    finally:
+        os.environ.pop("SKD_S_FFN2", None)
+    with skd.Decoder(cfg, w) as dec:                      # the same configuration without the override is fine
+        dec.prefill(S.make_prompts(2, 4, MID.V, 3))
+
+
 def test_vocabulary_above_sampler_limit():
     # the sampling head keeps a row of probabilities in registers: vocabularies above 65536 are refused with
     # SKD_ERR_SHAPE, while the LM head and greedy argmax have no such limit
