@@ -705,7 +705,8 @@ int bf16_gemm_ws(hipStream_t s, const GemmArgs &a, int epi, int R) {
 // land at the wave's LDS base + 16 * lane: fragments arrive ready-made and no
 // register holds data in flight), three stages ahead of the one being
 // multiplied.  Each wave accumulates a 64 x 128 sub-tile (4 x 8 MFMA tiles, 128
-// accumulator registers), reading 12 fragments from LDS per 32 MFMAs.
+// accumulator registers), reading 12 fragments from LDS per 32 MFMAs, one
+// k-step ahead of the MFMAs that use them.
 constexpr int TILE_NS = 4;   // ring stages
 constexpr int TILE_FR = 32;  // fragments per stage: 16 weight tiles, then 16 activation-row tiles
 
@@ -721,7 +722,7 @@ __device__ inline void wait_vmcnt_le(int n) {
 template <int EPI>
 __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   extern __shared__ bf16x8 tile_lds[];  // [TILE_NS stages][TILE_FR][64 lanes]
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wr = wave >> 1, wc = wave & 1;  // sub-tile: weight tiles 4wr .. 4wr+3, activation tiles 8wc .. 8wc+7
   const int Kf = a.K >> 5;
 
@@ -740,22 +741,26 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     }
   }
 
-  // this wave's share of a stage: 4 fragments; waves 0..3 fetch the weight tiles, waves 4..7 the activation tiles
+  // this wave's share of a stage: 4 fragments; waves 0..3 fetch the weight tiles, waves 4..7 the activation tiles.
+  // Fragment bases are wave-uniform (scalar registers); the only per-lane part of an address is the lane's place
+  // in the fragment, one 32-bit register.
   const int ld_is_a = wave >> 2, ld_t0 = (wave & 3) * 4;
   const bf16x8 *src[4];
   long sstride;
+  unsigned vlane;
   if (!ld_is_a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int T = tn * 16 + ld_t0 + i;
-      src[i] = (const bf16x8 *)a.W + (((long)(T / a.G) * Kf) * a.G + T % a.G) * 64 + lane;
+      src[i] = (const bf16x8 *)a.W + (((long)(T / a.G) * Kf) * a.G + T % a.G) * 64;
     }
     sstride = (long)a.G * 64;
+    vlane = lane;
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)  // fetched in MFMA lane order, so that LDS holds ready-made fragments
-      src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf) * 64 + act_lane(lane);
+    for (int i = 0; i < 4; ++i) src[i] = (const bf16x8 *)a.A + ((long)(tm * 16 + ld_t0 + i) * Kf) * 64;
     sstride = 64;
+    vlane = act_lane(lane);  // fetched in MFMA lane order, so that LDS holds ready-made fragments
   }
   const int dfrag = ld_is_a * 16 + ld_t0;
 
@@ -769,38 +774,90 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     bf16x8 *dst = tile_lds + ((st % TILE_NS) * TILE_FR + dfrag) * 64;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + (long)st * sstride),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)&(src[i] + (long)st * sstride)[vlane],
                                        (__attribute__((address_space(3))) void *)(dst + i * 64), 16, 0, 0);
   };
-  auto compute = [&](int buf) {
+  auto read = [&](int buf, bf16x8(&wf)[4], bf16x8(&xf)[8]) {  // 12 fragments of a stage into registers
     const bf16x8 *base = tile_lds + buf * (TILE_FR * 64) + lane;
-    bf16x8 wf[4], xf[8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) wf[r] = base[(wr * 4 + r) * 64];
 #pragma unroll
     for (int m = 0; m < 8; ++m) xf[m] = base[(16 + wc * 8 + m) * 64];
+  };
+  auto mma = [&](const bf16x8(&wf)[4], const bf16x8(&xf)[8]) {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
       for (int m = 0; m < 8; ++m) acc[r][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[r], xf[m], acc[r][m], 0, 0, 0);
   };
-
-#pragma unroll
-  for (int i = 0; i < TILE_NS - 1; ++i)
-    if (i < Kf) issue(i);
-  for (int st = 0; st < Kf; ++st) {
-    // This wave's loads of stage st have landed once at most the loads of the (up to two) later stages in flight
-    // are outstanding.  The barrier then says the same of every wave, and that every wave has finished reading
-    // the stage before st, whose ring slot the next loads overwrite.  It is a bare s_barrier between compiler
-    // fences: __syncthreads() would also wait for the loads of the later stages.  The LDS reads of compute()
-    // complete (lgkmcnt) before its MFMAs issue, so no wave reaches the next barrier with a read pending.
+  // Stage st becomes readable.  This wave's loads of it have landed once at most the loads of the (up to two)
+  // later stages in flight are outstanding, and its own LDS reads (of stage st - 1) have completed; the barrier
+  // then says both of every wave, so stage st may be read and the ring slot of stage st - 1 refilled.  It is a
+  // bare s_barrier between compiler fences: __syncthreads() would also wait for the loads of the later stages.
+  auto open_stage = [&](int st) {
     const int later = min(Kf - 1 - st, TILE_NS - 2);
     wait_vmcnt_le(4 * later);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (st + TILE_NS - 1 < Kf) issue(st + TILE_NS - 1);
-    compute(st % TILE_NS);
+  };
+
+#pragma unroll
+  for (int i = 0; i < TILE_NS - 1; ++i)
+    if (i < Kf) issue(i);
+  // Two register sets of fragments: while the matrix cores work on stage st out of one, the LDS reads of stage
+  // st + 1 fill the other.  With one set, every k-step began with all 8 waves waiting for 96 KiB of LDS reads
+  // (the barrier puts them in phase) while the matrix cores sat idle.
+  bf16x8 wfA[4], xfA[8], wfB[4], xfB[8];
+  open_stage(0);
+  read(0, wfA, xfA);
+  // Steady state (three later stages still to be requested): one straight-line block per k-step, in which the
+  // scheduler is told to deal the 12 LDS reads of the next stage out among the 32 MFMAs of the current one, so
+  // that a wave does not sit on a full LDS queue with MFMAs ready behind it (instructions issue in order).
+  auto steady = [&](int nx, bf16x8(&wn)[4], bf16x8(&xn)[8], const bf16x8(&wc_)[4], const bf16x8(&xc)[8]) {
+    wait_vmcnt_le(8);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(nx + TILE_NS - 1);
+    read(nx % TILE_NS, wn, xn);
+    mma(wc_, xc);
+    __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);  // the 4 LDS-direct loads first
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {  // the reads early: (MFMA, read) x 4, (MFMA x 2, read) x 8, then 12 MFMAs, so that
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // no read is still in flight when the wave reaches the
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // next barrier
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);
+  };
+  int st = 0;
+  for (; st + 5 < Kf; st += 2) {
+    steady(st + 1, wfB, xfB, wfA, xfA);
+    steady(st + 2, wfA, xfA, wfB, xfB);
+  }
+  for (; st < Kf; st += 2) {  // the last stages, where waits and requests depend on what is left
+    if (st + 1 < Kf) {
+      open_stage(st + 1);
+      read((st + 1) % TILE_NS, wfB, xfB);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mma(wfA, xfA);
+    if (st + 1 < Kf) {
+      if (st + 2 < Kf) {
+        open_stage(st + 2);
+        read((st + 2) % TILE_NS, wfA, xfA);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      mma(wfB, xfB);
+    }
   }
 
 #pragma unroll
