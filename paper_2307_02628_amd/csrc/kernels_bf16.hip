@@ -860,14 +860,112 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     }
   }
 
+  // ---- epilogue.  acc[r][m]: lane l holds output rows (weight rows) n0 .. n0 + 3 of activation row
+  // row0(m) + (l & 15), n0 = 16 * (weight tile) + 4 * (l >> 4).
+  const int grp = lane >> 4, j = lane & 15;
+  auto n0_of = [&](int r) { return ((tn * 16 + wr * 4 + r) << 4) + 4 * grp; };
+  auto row0_of = [&](int m) { return (tm * 16 + wc * 8 + m) << 4; };
+  if constexpr (EPI == EPI_RELU) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int n0 = ((tn * 16 + wr * 4 + r) << 4) + 4 * (lane >> 4);
-    EpiPre pre[8];
+    for (int r = 0; r < 4; ++r) {
+      const int n0 = n0_of(r);
+      EpiPre pre;
+      pre.bias = *(const floatx4 *)&a.bias[n0];
 #pragma unroll
-    for (int m = 0; m < 8; ++m) pre[m] = epi_prefetch<EPI>(a, ((tm * 16 + wc * 8 + m) << 4) + (lane & 15), n0);
+      for (int m = 0; m < 8; ++m) gemm_epilogue<EPI>(a, row0_of(m) + j, n0, acc[r][m], pre);
+    }
+  } else if constexpr (EPI == EPI_RESID) {
+    // the residual values of the next weight tile are requested before the current one is stored: one exposed
+    // round trip per workgroup instead of four
+    floatx4 xv[2][8];
+    auto fetch = [&](int r, floatx4(&x)[8]) {
 #pragma unroll
-    for (int m = 0; m < 8; ++m) gemm_epilogue<EPI>(a, ((tm * 16 + wc * 8 + m) << 4) + (lane & 15), n0, acc[r][m], pre[m]);
+      for (int m = 0; m < 8; ++m) x[m] = *(const floatx4 *)&a.x[(long)(row0_of(m) + j) * a.N + n0_of(r)];
+    };
+    auto store = [&](int r, const floatx4(&x)[8]) {
+      const floatx4 bias = *(const floatx4 *)&a.bias[n0_of(r)];
+#pragma unroll
+      for (int m = 0; m < 8; ++m) *(floatx4 *)&a.x[(long)(row0_of(m) + j) * a.N + n0_of(r)] = x[m] + (acc[r][m] + bias);
+    };
+    fetch(0, xv[0]);
+    fetch(1, xv[1]);
+    store(0, xv[0]);
+    fetch(2, xv[0]);
+    store(1, xv[1]);
+    fetch(3, xv[1]);
+    store(2, xv[0]);
+    store(3, xv[1]);
+  } else {  // EPI_QKV_ROWS
+    // The 256 output rows of a workgroup lie inside one of q | k | v (d is a multiple of 256 when 3 d is), and the
+    // 16 activation rows of a tile belong to one sequence and one page: what the stores need to know about a tile
+    // is wave-uniform and is looked up once, with scalar loads, not once per weight tile and lane.
+    const int which = (tn * 256) / a.d;
+    int t_page[8], t_slot0[8], t_len[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      t_page[m] = -1;
+      t_slot0[m] = 0;
+      t_len[m] = 0;
+      const int row0 = row0_of(m);
+      if (which != 0 && row0 < a.rows) {
+        const int b = a.rm.seq[row0];
+        if (b >= 0) {
+          t_slot0[m] = row0 - a.rm.first_row[b];  // = real position of the tile's first row
+          t_len[m] = a.rm.P - a.rm.start[b];      // positions of the sequence; the rest of its last tile is padding
+          if (t_slot0[m] < t_len[m]) t_page[m] = a.bt_layer[(long)b * a.kv.max_pages + t_slot0[m] / a.kv.page_tokens];
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int n0 = n0_of(r), within = n0 - which * a.d;
+      const floatx4 bias = *(const floatx4 *)&a.bias[n0];
+      const int h = within / a.kv.dh, e = within - h * a.kv.dh;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        floatx4 v = acc[r][m] + bias;
+        if (which == 0) {
+          if (row0_of(m) < a.rows)
+            *(uint2 *)&a.q_out[d_act_index(row0_of(m) + j, within, a.d)] = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+          continue;
+        }
+        if (t_page[m] < 0) continue;
+        bf16_t *pg = a.kv_pool + (long)t_page[m] * a.kv.page_elems;
+        const int tt = (t_slot0[m] + j) % a.kv.page_tokens;
+        if (which == 1) {
+          if (t_slot0[m] + j < t_len[m])
+            *(uint2 *)&pg[kv_k_off(h, tt, e, a.kv)] = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+          continue;
+        }
+        // v: a page holds, for one element e, four consecutive positions side by side.  The four lanes of a quad
+        // hold positions 4q .. 4q + 3 for elements e .. e + 3 each: transposed inside the quad (two exchanges,
+        // with the lane 1 and the lane 2 away), lane t ends up with element e + t of all four positions and
+        // stores them as one 8-byte word.
+        const int t = j & 3;
+        {
+          const float s0 = (t & 1) ? v[0] : v[1], s1 = (t & 1) ? v[2] : v[3];
+          const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s0), 0xB1, 0xF, 0xF, true));
+          const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s1), 0xB1, 0xF, 0xF, true));
+          if (t & 1) { v[0] = r0; v[2] = r1; } else { v[1] = r0; v[3] = r1; }
+        }
+        {
+          const float s0 = (t & 2) ? v[0] : v[2], s1 = (t & 2) ? v[1] : v[3];
+          const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s0), 0x4E, 0xF, 0xF, true));
+          const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s1), 0x4E, 0xF, 0xF, true));
+          if (t & 2) { v[0] = r0; v[1] = r1; } else { v[2] = r0; v[3] = r1; }
+        }
+        // now v[s] = element e + t of position 4 * (j / 4) + s
+        const int pos0 = t_slot0[m] + (j & ~3), nvalid = t_len[m] - pos0;
+        bf16_t *dst = &pg[kv_v_off(h, pos0 % a.kv.page_tokens, e + t, a.kv)];
+        if (nvalid >= 4) {
+          *(uint2 *)dst = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+        } else {
+          for (int s_ = 0; s_ < 4; ++s_)
+            if (s_ < nvalid) dst[s_] = (bf16_t)f2bf(v[s_]);
+        }
+        (void)tt;
+      }
+    }
   }
 }
 
