@@ -177,7 +177,10 @@ def run_generation(skd, torch, shape, w, B, P, T, n_min, n_max, mask, steps, war
             t = {k: a.elapsed_time(b) for k, a, b in pairs}
             rep_ms.append(sum(t[k] for k in ks))
             first_ms.append(t[0])
+    # projections of the prompt pass: 2 flops per weight and real prompt token, all L layers (attention not counted)
+    prefill_flop = 2.0 * float(P * B - start.sum()) * shape.L * (4 * shape.d * shape.d + 2 * shape.d * shape.f)
     out = {"rep_ms": rep_ms, "first_step_ms": first_ms, "prefill_s": prefill_s, "ks": ks,
+           "prefill_projection_pflops": prefill_flop / prefill_s / 1e15,
            "layers": [layers[k] for k in ks], "sum_len": [sum_len[k] for k in ks],
            "bytes": sum(step_bytes(shape, layers[k], sum_len[k]) for k in ks),
            "kv_pages": dec.kv_pages()}
@@ -254,7 +257,7 @@ def measure_workload(skd, torch, name, w, steps, warmup, reps, profile, args):
                    "sum_n": int(sum(skip["layers"])), "mean_n": float(np.mean(skip["layers"]))},
         "hbm_gbs": gbs, "hbm_frac_of_8TBs": gbs / HBM_PEAK_GBS,
         "algorithmic_gb_per_step": skip["bytes"] / n_timed / 1e9,
-        "prefill_s": skip["prefill_s"],
+        "prefill_s": skip["prefill_s"], "prefill_projection_pflops": skip["prefill_projection_pflops"],
         "kv_pages_reserved_vs_dense": list(skip["kv_pages"]),
         "ms_per_step_repeats": {"n": int(r.size), "median": float(np.median(r)), "min": float(r.min()),
                                 "max": float(r.max())},
@@ -437,7 +440,7 @@ def main():
         o = measure_workload(skd, torch, name, weights_of(WORKLOADS[name][0]), args.steps, args.warmup,
                              max(3, args.reps // 2 + 1), not args.no_profile, args)
         keep = ("value", "unit", "steps", "ms_per_step", "hbm_gbs", "hbm_frac_of_8TBs", "algorithmic_gb_per_step",
-                "prefill_s", "speedup_vs_full_depth", "ideal_layer_ratio", "ideal_byte_ratio",
+                "prefill_s", "prefill_projection_pflops", "speedup_vs_full_depth", "ideal_layer_ratio", "ideal_byte_ratio",
                 "ms_per_step_repeats", "equal_depth_step_ms")
         others[name] = {k: o[k] for k in keep if k in o}
         others[name]["config"] = o["config"]
