@@ -1340,106 +1340,159 @@ void bf16_attention(hipStream_t s, const AttnArgs &a) {
 // ------------------------------------------------------------------ causal attention over a whole prompt
 // Same block arithmetic as k_attention, but the 16 MFMA columns now carry 16
 // different queries (consecutive positions of one sequence) instead of one
-// replicated query.  A workgroup takes 64 consecutive rows of the prompt pass
-// for one head: each of its 4 waves owns one 16-position tile (of one sequence)
-// and walks all key blocks of that tile itself (no merge; softmax state per column), and since
-// the four waves read almost the same keys at almost the same time, all but
-// the first of those loads are cache hits (L2 at worst).  Keys: real positions 0 .. own.
-template <int DH>
-__global__ __launch_bounds__(256) void k_attention_rows(AttnRowsArgs a) {
+// replicated query.  A wave owns NT = 2 consecutive 16-position tiles of one
+// sequence and one head when both exist (every K and V fragment it loads then
+// serves 32 queries: the kernel is bound by what the vector memory path delivers
+// to registers, 64 bytes per clock and CU, so bytes per query are what counts),
+// else one tile; it walks all key blocks of its tiles itself (no merge; softmax
+// state per column), loading the keys of block i + 1 while it works on block i.  A workgroup
+// is 4 waves on 128 consecutive rows: they read almost the same keys at almost
+// the same time, so all but the first of those loads are cache hits (L2 at
+// worst).  Keys of a query: real positions 0 .. own.
+template <int DH, int NT>
+__device__ inline void attention_rows_tiles(const AttnRowsArgs &a, int h, long row0, int b) {
   constexpr int QC = DH / 32, VM = DH / 16;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane >> 4, col = lane & 15;
-  const int H = a.kv.H, h = blockIdx.x, d = H * DH;
-  const long row0 = ((long)blockIdx.y * 4 + wave) * 16;  // first row of this wave's tile
-  if (row0 >= a.rows) return;                            // (no barriers below)
-  const int b = a.rm.seq[row0];
-  if (b < 0) return;                                     // rows past the last sequence
-  const int p0 = (int)(row0 - a.rm.first_row[b]);        // real position of the tile's first query
+  const int lane = threadIdx.x & 63, grp = lane >> 4, col = lane & 15;
+  const int d = a.kv.H * DH;
+  const int p0 = (int)(row0 - a.rm.first_row[b]);        // real position of the first query
   const int len = a.rm.P - a.rm.start[b];                // real positions of this sequence
-  const int my_pos = p0 + col;                           // this column's query position
-  const int last = min(p0 + 15, len - 1);                // last real position of the tile
-  const int my_len = my_pos + 1;                         // keys of this query: real positions 0 .. my_pos
-  const int blk_lo = 0, blk_hi = (last >> 5) + 1;
+  const int last = min(p0 + 16 * NT - 1, len - 1);       // last real position of the tiles
+  const int nblk = (last >> 5) + 1;
   const int bpp = a.kv.page_tokens >> 5;
   const int32_t *bt_row = a.bt_layer + (long)b * a.kv.max_pages;
   const float scale = 1.0f / sqrtf((float)DH);
 
-  bf16x8 qf[QC];
+  bf16x8 qf[NT][QC];
 #pragma unroll
-  for (int c = 0; c < QC; ++c)
-    qf[c] = ((const bf16x8 *)a.q)[((row0 >> 4) * (d >> 5) + ((h * DH) >> 5) + c) * 64 + act_lane(lane)];
-
-  floatx4 O[VM];
+  for (int t = 0; t < NT; ++t)
 #pragma unroll
-  for (int m = 0; m < VM; ++m) O[m] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -1.0e30f, l_run = 0.f;
+    for (int c = 0; c < QC; ++c)
+      qf[t][c] = ((const bf16x8 *)a.q)[(((row0 >> 4) + t) * (d >> 5) + ((h * DH) >> 5) + c) * 64 + act_lane(lane)];
 
-  for (int blk = blk_lo; blk < blk_hi; ++blk) {
+  floatx4 O[NT][VM];
+  float m_run[NT], l_run[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    m_run[t] = -1.0e30f;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int m = 0; m < VM; ++m) O[t][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  auto blk_ptr = [&](int blk) {
     const int page = bt_row[blk / bpp];
-    const bf16x8 *kp = (const bf16x8 *)(a.pool + (long)page * a.kv.page_elems + (long)h * (a.kv.page_tokens * DH * 2) +
-                                        (long)(blk % bpp) * (64 * DH)) + lane;
-    bf16x8 kf[2][QC], vf[VM];
+    return (const bf16x8 *)(a.pool + (long)page * a.kv.page_elems + (long)h * (a.kv.page_tokens * DH * 2) +
+                            (long)(blk % bpp) * (64 * DH)) + lane;
+  };
+  auto load_k = [&](int blk, bf16x8(&kf)[2][QC]) {
+    const bf16x8 *kp = blk_ptr(blk);
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
       for (int c = 0; c < QC; ++c) kf[tl][c] = kp[(tl * QC + c) * 64];
+  };
+  auto load_v = [&](int blk, bf16x8(&vf)[VM]) {
+    const bf16x8 *kp = blk_ptr(blk);
 #pragma unroll
     for (int m = 0; m < VM; ++m) vf[m] = kp[4 * DH + m * 64];
-    floatx4 S[2];
+  };
+  auto use_blk = [&](int blk, const bf16x8(&kf)[2][QC], const bf16x8(&vf)[VM]) {
 #pragma unroll
-    for (int tl = 0; tl < 2; ++tl) {
-      S[tl] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t) {
+      const int my_len = p0 + 16 * t + col + 1;  // keys of this column's query: real positions 0 .. own
+      if (NT > 1 && t == 0 && blk * 32 > p0 + 15) continue;  // (uniform) the block lies past the first tile's keys
+      floatx4 S[2];
 #pragma unroll
-      for (int c = 0; c < QC; ++c) S[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tl][c], qf[c], S[tl], 0, 0, 0);
-    }
-    float sv[8];
-    bool ok[8];
-    float bm = -1.0e30f;
+      for (int tl = 0; tl < 2; ++tl) {
+        S[tl] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = blk * 32 + 16 * tl + 4 * grp + i;
-        ok[tl * 4 + i] = key < my_len;
-        sv[tl * 4 + i] = S[tl][i] * scale;
-        if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
+        for (int c = 0; c < QC; ++c) S[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tl][c], qf[t][c], S[tl], 0, 0, 0);
       }
-    bm = fmaxf(bm, __shfl_xor(bm, 16));  // lanes 16 and 32 apart hold the same query column
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
-    const float m_new = fmaxf(m_run, bm);
-    const float alpha = __expf(m_run - m_new);
-    float ps = 0.f;
-    uint32_t pk[4];
+      float sv[8];
+      bool ok[8];
+      float bm = -1.0e30f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float p_lo = ok[2 * j] ? __expf(sv[2 * j] - m_new) : 0.f;
-      const float p_hi = ok[2 * j + 1] ? __expf(sv[2 * j + 1] - m_new) : 0.f;
-      pk[j] = pack2(p_lo, p_hi);
-      ps += bf2f(pk[j] & 0xffffu) + bf2f(pk[j] >> 16);
+      for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int key = blk * 32 + 16 * tl + 4 * grp + i;
+          ok[tl * 4 + i] = key < my_len;
+          sv[tl * 4 + i] = S[tl][i] * scale;
+          if (ok[tl * 4 + i]) bm = fmaxf(bm, sv[tl * 4 + i]);
+        }
+      bm = fmaxf(bm, __shfl_xor(bm, 16));  // lanes 16 and 32 apart hold the same query column
+      bm = fmaxf(bm, __shfl_xor(bm, 32));
+      const float m_new = fmaxf(m_run[t], bm);
+      const float alpha = __expf(m_run[t] - m_new);
+      float ps = 0.f;
+      uint32_t pk[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float p_lo = ok[2 * j] ? __expf(sv[2 * j] - m_new) : 0.f;
+        const float p_hi = ok[2 * j + 1] ? __expf(sv[2 * j + 1] - m_new) : 0.f;
+        pk[j] = pack2(p_lo, p_hi);
+        ps += bf2f(pk[j] & 0xffffu) + bf2f(pk[j] >> 16);
+      }
+      l_run[t] = l_run[t] * alpha + ps;
+      m_run[t] = m_new;
+      const uint32x4 pku = uint32x4{pk[0], pk[1], pk[2], pk[3]};
+      const bf16x8 pv = __builtin_bit_cast(bf16x8, pku);
+#pragma unroll
+      for (int m = 0; m < VM; ++m) {
+        O[t][m] *= alpha;
+        O[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[m], pv, O[t][m], 0, 0, 0);
+      }
     }
-    l_run = l_run * alpha + ps;
-    m_run = m_new;
-    const uint32x4 pku = uint32x4{pk[0], pk[1], pk[2], pk[3]};
-    const bf16x8 pv = __builtin_bit_cast(bf16x8, pku);
-#pragma unroll
-    for (int m = 0; m < VM; ++m) {
-      O[m] *= alpha;
-      O[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[m], pv, O[m], 0, 0, 0);
+  };
+
+  // keys one block ahead (two register sets), values requested at the top of their block: they are not needed
+  // before the scores and the softmax of the first tile are done
+  bf16x8 kA[2][QC], kB[2][QC], vf[VM];
+  load_k(0, kA);
+  for (int blk = 0; blk < nblk; blk += 2) {
+    load_v(blk, vf);
+    if (blk + 1 < nblk) load_k(blk + 1, kB);
+    use_blk(blk, kA, vf);
+    if (blk + 1 < nblk) {
+      load_v(blk + 1, vf);
+      if (blk + 2 < nblk) load_k(blk + 2, kA);
+      use_blk(blk + 1, kB, vf);
     }
   }
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  // O[m][i] = numerator of query `col`, head-dim element 16m + 4grp + i
-  const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
 #pragma unroll
-  for (int m = 0; m < VM; ++m) {
-    const uint2 pk = make_uint2(pack2(O[m][0] * inv, O[m][1] * inv), pack2(O[m][2] * inv, O[m][3] * inv));
-    *(uint2 *)&a.o[d_act_index(row0 + col, h * DH + 16 * m + 4 * grp, d)] = pk;
+  for (int t = 0; t < NT; ++t) {
+    float l = l_run[t];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    // O[t][m][i] = numerator of query `col` of tile t, head-dim element 16m + 4grp + i
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+    for (int m = 0; m < VM; ++m) {
+      const uint2 pk = make_uint2(pack2(O[t][m][0] * inv, O[t][m][1] * inv), pack2(O[t][m][2] * inv, O[t][m][3] * inv));
+      *(uint2 *)&a.o[d_act_index(row0 + 16 * t + col, h * DH + 16 * m + 4 * grp, d)] = pk;
+    }
   }
 }
 
+template <int DH>
+__global__ __launch_bounds__(256, 2) void k_attention_rows(AttnRowsArgs a) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int h = blockIdx.x;
+  const long row0 = ((long)blockIdx.y * 4 + wave) * 32;  // first row of this wave's pair of tiles (no barriers below)
+  // rows past the last sequence carry -1; a sequence's rows are whole 16-row tiles, so the second tile of a pair may
+  // belong to the next sequence
+  const int b0 = row0 < a.rows ? a.rm.seq[row0] : -1;
+  const int b1 = row0 + 16 < a.rows ? a.rm.seq[row0 + 16] : -1;
+  if (b0 >= 0 && b1 == b0) {
+    attention_rows_tiles<DH, 2>(a, h, row0, b0);
+    return;
+  }
+  if (b0 >= 0) attention_rows_tiles<DH, 1>(a, h, row0, b0);
+  if (b1 >= 0) attention_rows_tiles<DH, 1>(a, h, row0 + 16, b1);
+}
+
 void bf16_attention_rows(hipStream_t s, const AttnRowsArgs &a) {
-  const dim3 grid(a.kv.H, (a.rows + 63) / 64);
+  const dim3 grid(a.kv.H, (a.rows + 127) / 128);
   if (a.kv.dh == 64) SKD_LAUNCH(k_attention_rows<64>, grid, dim3(256), 0, s, a);
   else SKD_LAUNCH(k_attention_rows<128>, grid, dim3(256), 0, s, a);
 }
