@@ -476,6 +476,42 @@ def test_prompt_tiles_in_xcd_order_page_contents():
     odec.close()
 
 
+def test_prompt_tiles_ragged_head_dim_64():
+    # The tiled prompt path on a ragged batch with 64-wide heads: 22 sequences whose real positions, padded to whole
+    # 16-row tiles, make exactly 1024 rows (grids 6 x 4, 2 x 4, 4 x 4: the XCD-aware order).  Lengths leave 1, 2 and 3
+    # valid positions in the last group of four (values are filed four positions at a time), sequences of 1 and 3
+    # tiles put the tile pairs of the prompt attention across sequence boundaries.  Logits per step and every cached
+    # key and value of the real positions against the oracle.
+    shape = S.ModelShape(L=2, d=512, H=8, f=1024, V=1000, max_pos=96)
+    lens = [61, 47, 33, 18, 64, 50, 35, 3, 62, 21, 64, 49, 31, 17, 63, 45, 2, 29, 57, 13, 64, 46]
+    B, P, N = len(lens), 64, 68
+    assert sum((n + 15) // 16 * 16 for n in lens) == 1024
+    assert {n % 4 for n in lens} == {0, 1, 2, 3}
+    mask = np.zeros((B, P), dtype=np.uint8)
+    for b, n in enumerate(lens):
+        mask[b, P - n:] = 1
+    w = bf16_weights(shape, 61)
+    pr = S.make_prompts(B, P, shape.V, 62)
+    tape = S.make_token_tape(B, N - P, shape.V, 63)
+    compare(shape, w, pr, P, N, 1, 2, BF16_TOL, mask=mask, dtype=skd.BF16, page_tokens=32, tape=tape, min_decided=0.0)
+    odec = O.Decoder(shape, w, B, N)
+    for i in range(P):
+        odec.column(i, pr[:, i], list(range(shape.L)), mask[:, i], want_logits=False)
+    cfg = skd.make_config(shape, B, P, N, 1, 2, page_tokens=32)
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr, mask)
+        for l in range(shape.L):
+            assert dec.kv_len(l) == odec.kv_len(l) == P
+            for b in range(B):
+                K, V = dec.kv_read(l, b)
+                Ko, Vo = odec.kv_read(l, b)
+                sl = slice(P - lens[b], P)                   # padded columns are never read: not compared
+                scale = max(np.abs(Ko[sl]).max(), np.abs(Vo[sl]).max())
+                assert np.abs(K[sl] - Ko[sl]).max() <= 2e-2 * scale, (l, b)
+                assert np.abs(V[sl] - Vo[sl]).max() <= 2e-2 * scale, (l, b)
+    odec.close()
+
+
 @pytest.mark.parametrize("env", [
     {"SKD_R_QKV": "1", "SKD_R_FFN1": "2", "SKD_R_HEAD": "3", "SKD_R_OUT": "1", "SKD_R_FFN2": "2"},
     {"SKD_U_QKV": "2", "SKD_U_FFN1": "4", "SKD_U_HEAD": "2", "SKD_U_OUT": "2", "SKD_U_FFN2": "4"},
