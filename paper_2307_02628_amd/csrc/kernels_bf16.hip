@@ -729,17 +729,25 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   const int Kf = a.K >> 5;
 
   // workgroup -> output tile.  Workgroups are dealt to the 8 XCDs round-robin; the ones that share an XCD (and
-  // its L2) at any moment should share operands, so each XCD walks its own contiguous range of tiles in blocks
-  // of 4 activation tiles x all weight tiles, weight tile fastest in groups of 4 rows.
-  int tn = blockIdx.x, tm = blockIdx.y;
+  // its L2) at any moment should share operands, so each XCD walks its own contiguous range of tiles in bands
+  // of 4 activation tiles x all weight tiles, weight tile fastest in groups of 4 rows (the last band has the
+  // gy % 4 activation tiles that are left; XCD x owns the workgroups with id % 8 == x, one more than the others
+  // when x < total % 8).
+  int tn, tm;
   {
     const int gx = gridDim.x, gy = gridDim.y, total = gx * gy;
-    if ((total & 7) == 0 && (gy & 3) == 0) {
-      const int id = blockIdx.x + gx * blockIdx.y;
-      const int logical = (id & 7) * (total >> 3) + (id >> 3);
+    const int id = blockIdx.x + gx * blockIdx.y;
+    const int xcd = id & 7, per = total >> 3, rem = total & 7;
+    const int logical = xcd * per + min(xcd, rem) + (id >> 3);
+    const int full = gy >> 2, tail0 = full * 4 * gx;
+    if (logical < tail0) {
       const int band = logical / (4 * gx), within = logical - band * 4 * gx;
       tn = within >> 2;
       tm = band * 4 + (within & 3);
+    } else {
+      const int hb = gy & 3, within = logical - tail0;  // hb > 0 here
+      tn = within / hb;
+      tm = full * 4 + within % hb;
     }
   }
 

@@ -100,7 +100,8 @@ def _prompt_grid(lens, N_out):
 
 
 def _takes_xcd_order(gx, gy):
-    """The tile kernel deals its workgroups to the 8 XCDs in bands of 4 activation tiles only for such grids."""
+    """Grids of the benchmark's kind: a multiple of the 8 XCDs and whole bands of 4 activation tiles (other grids
+    get a shorter last band and uneven shares, tests/test_gpu_parity.py covers those)."""
     return (gx * gy) % 8 == 0 and gy % 4 == 0
 
 

@@ -476,6 +476,33 @@ def test_prompt_tiles_in_xcd_order_page_contents():
     odec.close()
 
 
+@pytest.mark.parametrize("B", [20, 28])
+def test_prompt_tiles_partial_band(B):
+    # 1280 and 1792 prompt rows: 5 and 7 activation tiles, i.e. one full band of 4 and a last band of 1 or 3 in the
+    # tile order of the prompt GEMM, with grid sizes (30, 10; 42, 14) that are no multiple of the 8 XCDs.  Every tile
+    # must still be computed exactly once: logits per step and every cached key and value against the oracle.
+    shape = MID
+    P, N = 64, 67
+    assert (B * P) % 256 == 0 and ((B * P) // 256) % 4 != 0
+    w = bf16_weights(shape, 71)
+    pr = S.make_prompts(B, P, shape.V, 72)
+    tape = S.make_token_tape(B, N - P, shape.V, 73)
+    compare(shape, w, pr, P, N, 1, 3, BF16_TOL, dtype=skd.BF16, page_tokens=32, tape=tape, min_decided=0.0)
+    odec = O.Decoder(shape, w, B, N)
+    for i in range(P):
+        odec.column(i, pr[:, i], list(range(shape.L)), want_logits=False)
+    cfg = skd.make_config(shape, B, P, N, 1, 3, page_tokens=32)
+    with skd.Decoder(cfg, w) as dec:
+        dec.prefill(pr)
+        for l in range(shape.L):
+            for b in range(B):
+                K, V = dec.kv_read(l, b)
+                Ko, Vo = odec.kv_read(l, b)
+                scale = max(np.abs(Ko).max(), np.abs(Vo).max())
+                assert np.abs(K - Ko).max() <= 2e-2 * scale and np.abs(V - Vo).max() <= 2e-2 * scale, (l, b)
+    odec.close()
+
+
 def test_prompt_tiles_ragged_head_dim_64():
     # The tiled prompt path on a ragged batch with 64-wide heads: 22 sequences whose real positions, padded to whole
     # 16-row tiles, make exactly 1024 rows (grids 6 x 4, 2 x 4, 4 x 4: the XCD-aware order).  Lengths leave 1, 2 and 3
